@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the MixLLM quantized linear hot path on one MI355X.
+
+A "step" is one pass of the whole hot path (activation quantizer + mixed W4/W8-A8 linear)
+over the four linear layers of one Llama-3-8B decoder block (QKV, O, gate+up, down) at M
+tokens, on seeded synthetic inputs that are already resident in HBM.  Weight buffers are
+rotated over several copies so that no step finds its weights in the 256 MB memory-side cache.
+
+Default run:  decode leg (M = 1; the `value` of the JSON line, in GB/s of algorithmic bytes)
+followed by short extra legs (other decode M, prefill M = 2048 in TOPS) that are reported in
+the same JSON line under "sweep" / "prefill".  `--workload prefill` makes the prefill leg the
+primary one.  One JSON line is printed on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+MALL_BYTES = 256 << 20
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def layer_alg_bytes(K, N, n8, M):
+    """Algorithmic bytes of one linear launch: every stored weight byte once (4-bit rows:
+    K/2 + 2.5 K/128; 8-bit rows: K + 2; 4 B of channel index per row), activations and
+    token scales in, fp16 outputs out."""
+    n4 = N - n8
+    w = n4 * (K // 2 + 2.5 * K / 128) + n8 * (K + 2) + 4 * N
+    return w + M * K + 2 * M + 2 * M * N
+
+
+def quant_alg_bytes(K, M):
+    return 2 * M * K + M * K + 2 * M
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode")
+    ap.add_argument("--m", type=int, default=None, help="tokens (default 1 for decode, 2048 for prefill)")
+    ap.add_argument("--no-extras", action="store_true", help="primary leg only (for profiling)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build is single-GPU by construction (one process, one MI355X); "
+            "--gpus above 1 is not supported")
+        sys.exit(2)
+
+    import torch
+    import paper_2412_14590_amd as mx
+    from paper_2412_14590_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    mx.lib()   # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    M0 = args.m if args.m is not None else (1 if args.workload == "decode" else 2048)
+
+    # ---- inputs (seeded, synthetic, Llama-3-8B shaped) -----------------------------------
+    t0 = time.time()
+    layers = []
+    for name, K, N, sigma, n_out in synth.model_layers("8b"):
+        lay = synth.make_layer(name, K, N, sigma=sigma, n_outlier_rows=n_out, seed=0)
+        layers.append(lay)
+        log(f"[bench] layer {name}: K={K} N={N} n8={lay.n8}  ({time.time() - t0:.1f}s)")
+    packed0 = [mx.quantize_weights(torch.from_numpy(l.W).to(dev), l.salient_idx) for l in layers]
+    torch.cuda.synchronize()
+    set_bytes = sum(p.weight_bytes() for p in packed0)
+    n_copies = max(2, -(-2 * MALL_BYTES // set_bytes))      # rotate over >= 512 MB of weights
+    copies = [packed0] + [[p.clone() for p in packed0] for _ in range(n_copies - 1)]
+    log(f"[bench] packed weights {set_bytes / 1e6:.1f} MB per block, {n_copies} rotating copies")
+
+    def make_acts(M):
+        xs_ = [torch.from_numpy(synth.make_x(M, l.K, seed=7, tag="x/" + l.name)).to(dev) for l in layers]
+        bufs = [(torch.empty((M, l.K), dtype=torch.int8, device=dev),
+                 torch.empty((M, 1), dtype=torch.float16, device=dev),
+                 torch.empty((M, l.N), dtype=torch.float16, device=dev)) for l in layers]
+        return xs_, bufs
+
+    def step(i, xs_, bufs):
+        ws = copies[i % n_copies]
+        for li in range(len(layers)):
+            xq, xsc, y = bufs[li]
+            mx.quantize_activations(xs_[li], out=(xq, xsc))
+            mx.mixed_linear(xq, xsc, ws[li], out=y)
+
+    def time_steps(M, steps, warmup):
+        xs_, bufs = make_acts(M)
+        for i in range(warmup):
+            step(i, xs_, bufs)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(steps):
+            step(i, xs_, bufs)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / steps
+
+    def time_dominant(M, reps, li):
+        """Average duration of one launch of the linear kernel of layer `li`, each launch
+        bracketed by its own pair of HIP events on the launch stream."""
+        xs_, bufs = make_acts(M)
+        xq, xsc, y = bufs[li]
+        mx.quantize_activations(xs_[li], out=(xq, xsc))
+        for i in range(10):
+            mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(evs):
+            a.record()
+            mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+            b.record()
+        torch.cuda.synchronize()
+        ts = np.array([a.elapsed_time(b) for a, b in evs]) * 1e-3
+        # and back to back between one pair of events (includes launch gaps)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+        b.record()
+        torch.cuda.synchronize()
+        return float(ts.mean()), float(np.median(ts)), a.elapsed_time(b) * 1e-3 / reps
+
+    def step_bytes(M):
+        return sum(layer_alg_bytes(l.K, l.N, l.n8, M) + quant_alg_bytes(l.K, M) for l in layers)
+
+    def step_ops(M):
+        return sum(2.0 * M * l.K * l.N for l in layers)
+
+    dom = max(range(len(layers)), key=lambda i: layers[i].K * layers[i].N)   # gate_up
+
+    def leg(M, steps, warmup, reps):
+        sec = time_steps(M, steps, warmup)
+        k_mean, k_med, k_b2b = time_dominant(M, reps, dom)
+        l = layers[dom]
+        out = {"M": M, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9,
+               "TOPS": step_ops(M) / sec / 1e12,
+               "dominant_kernel": {"layer": l.name, "us_event_mean": k_mean * 1e6, "us_event_median": k_med * 1e6,
+                                   "us_back_to_back": k_b2b * 1e6,
+                                   "GBps": layer_alg_bytes(l.K, l.N, l.n8, M) / k_mean / 1e9,
+                                   "TOPS": 2.0 * M * l.K * l.N / k_mean / 1e12}}
+        log(f"[bench] M={M}: {out['ms_per_step']:.4f} ms/step, {out['GBps']:.0f} GB/s, {out['TOPS']:.1f} TOPS; "
+            f"{l.name} kernel {k_mean * 1e6:.1f} us (median {k_med * 1e6:.1f}, b2b {k_b2b * 1e6:.1f})")
+        return out
+
+    primary = leg(M0, args.steps, args.warmup, min(args.steps, 200))
+    decode_like = M0 <= 16
+    l = layers[dom]
+    if decode_like:
+        roof = {"bound": "hbm", "achieved": primary["dominant_kernel"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": primary["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = f"mixed_linear {'decode' if decode_like else 'prefill'} path, layer {l.name} K={l.K} N={l.N} M={M0}"
+    roof["us_per_launch"] = primary["dominant_kernel"]["us_event_mean"]
+
+    result = {
+        "metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)",
+        "value": primary["GBps"] if decode_like else primary["TOPS"],
+        "unit": "GB/s" if decode_like else "TOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": primary["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"Llama-3-8B-shaped decoder-block linears (QKV, O, gate+up, down), "
+                               f"{'decode' if decode_like else 'prefill'} M={M0}, 10% int8 channels, int4 g128, "
+                               f"per-token int8 activations, fp16 out",
+                   "M": M0, "weight_copies_rotated": n_copies},
+        "step_GBps": primary["GBps"], "step_TOPS": primary["TOPS"],
+        "roofline": roof,
+    }
+
+    # ---- extra legs ------------------------------------------------------------------------
+    if not args.no_extras:
+        sweep = []
+        for M in ([4, 8, 16] if decode_like else [512]):
+            sweep.append(leg(M, max(20, args.steps // 4), 5, 50))
+        result["sweep"] = sweep
+        other = leg(2048 if decode_like else 1, 20 if decode_like else 100, 3, 30)
+        key = "prefill" if decode_like else "decode"
+        if decode_like:
+            other["roofline"] = {"bound": "mfma", "achieved": other["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS,
+                                 "unit": "TOP/s", "frac": other["dominant_kernel"]["TOPS"] / INT8_PEAK_TOPS}
+        else:
+            other["roofline"] = {"bound": "hbm", "achieved": other["dominant_kernel"]["GBps"], "peak": HBM_PEAK_GBS,
+                                 "unit": "GB/s", "frac": other["dominant_kernel"]["GBps"] / HBM_PEAK_GBS}
+        result[key] = other
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample ---------------------------
+    if not args.no_cpu:
+        from oracle import ref
+        t1 = time.time()
+        Ms = M0 if decode_like else 8       # prefill: a sample of 8 token rows of the same layers
+        Ls = [ref.quantize_weights(l.W, l.salient_idx) for l in layers]
+        log(f"[bench] oracle weight quantization {time.time() - t1:.1f}s (not timed)")
+        xs_h = [synth.make_x(Ms, l.K, seed=7, tag="x/" + l.name) for l in layers]
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 50:
+            t = time.perf_counter()
+            for xh, L in zip(xs_h, Ls):
+                xq, xsc = ref.quantize_act(xh)
+                ref.mixed_linear(xq, xsc, L)
+            t_cpu += time.perf_counter() - t
+            reps += 1
+        sec = t_cpu / reps
+        val = (step_bytes(Ms) / sec / 1e9) if decode_like else (step_ops(Ms) / sec / 1e12)
+        result["cpu_baseline"] = {"value": val, "unit": result["unit"], "cores": ref.num_threads(), "kind": "oracle",
+                                  "sample": f"{reps} passes of the same 4 layers at M={Ms} tokens "
+                                            f"({sec * 1e3:.1f} ms per pass), all channels, all groups"}
+        log(f"[bench] cpu oracle: {val:.3g} {result['unit']} on {ref.num_threads()} threads")
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

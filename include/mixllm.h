@@ -1,0 +1,186 @@
+/*
+ * mixllm.h -- C ABI of the MI355X (gfx950) implementation of the MixLLM quantized
+ * linear layer (arxiv 2412.14590): weights mix bit-widths between OUTPUT features
+ * (Sec. 3.1.1): a salient set of n8 output channels is int8 symmetric, the other
+ * N - n8 channels are uint4 asymmetric with one fp16 scale and one uint4 zero point
+ * per group of 128 input features; activations are int8 symmetric (Sec. 3.1.2,
+ * Sec. 4.1).  The linear is a fused dequantize + int8 MatMul with an int32 partial
+ * sum per quantization group, rescaled in float (two-step dequantization, Sec. 3.3),
+ * and both parts scatter into one output tensor in the original channel order
+ * (Sec. 3.4).
+ *
+ * Conventions
+ *   - Every function returns an int status: MIXLLM_OK or a negative error code.
+ *     Arguments are validated on the host BEFORE anything is launched, so an error
+ *     return means nothing ran.  No function throws.
+ *   - Unless a parameter says "host", every data pointer is DEVICE memory, owned by
+ *     the caller, 16-byte aligned, of the size mixllm_query_sizes() reports.  The
+ *     library allocates no device memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it and the call returns without synchronizing, except where stated.
+ *   - fp16 values are IEEE binary16, stored as 2-byte words.
+ *   - Inputs holding Inf or NaN are not supported (results unspecified, no fault).
+ *
+ * Granularity variants (mixllm_desc):
+ *   act_group = K   one activation scale per token          (default workload)
+ *   act_group = 128 one activation scale per (token, group) (the paper's Sec. 3.1.2 choice)
+ *   w8_group  = K   one scale per 8-bit channel             (default workload)
+ *   w8_group  = 128 one scale per (8-bit channel, group)    (the paper's Sec. 4.1 choice)
+ * The integer partial sums are the same in every variant; only the scale lookup changes.
+ */
+#ifndef MIXLLM_H
+#define MIXLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MIXLLM_GROUP 128
+
+enum {
+    MIXLLM_OK = 0,
+    MIXLLM_EINVAL = -1,       /* null or misaligned pointer, negative size, bad index list */
+    MIXLLM_EUNSUPPORTED = -2, /* shape or variant the kernels do not cover (e.g. K % 128 != 0) */
+    MIXLLM_EWORKSPACE = -3,   /* workspace smaller than mixllm_query_sizes() asked for */
+    MIXLLM_EHIP = -4          /* a HIP runtime call failed (launch error, bad stream, ...) */
+};
+
+/* Kernel selection for the entry points that take a `path` argument. */
+enum {
+    MIXLLM_PATH_AUTO = 0,    /* decode path for M <= 16, tiled MFMA path otherwise */
+    MIXLLM_PATH_GENERIC = 1, /* one thread per output element, no MFMA; any shape; slow */
+    MIXLLM_PATH_DECODE = 2,  /* weight-streaming path, M <= 16 */
+    MIXLLM_PATH_PREFILL = 3  /* LDS-staged tiled MFMA path, any M */
+};
+
+typedef struct mixllm_desc {
+    int32_t M;         /* tokens (rows of x and y); may be 0 for the offline calls */
+    int32_t K;         /* input features, multiple of 128 */
+    int32_t N;         /* output features */
+    int32_t n8;        /* how many of the N output channels are int8, 0..N */
+    int32_t group;     /* quantization group size along K for the uint4 part: must be 128 */
+    int32_t act_group; /* K or 128, see above */
+    int32_t w8_group;  /* K or 128, see above */
+} mixllm_desc;
+
+/*
+ * Buffer sizes in bytes.  Packed layouts (opaque to callers; use pack/unpack to cross):
+ *   rows of each part are padded to a multiple of 16 (n8p, n4p), groups of metadata to a
+ *   multiple of 8 (ngp), padding is zero-filled by the library.
+ *   packed_w8  [n8p/16][K/64][64][16 B]  int8; 16-row tile x 64-k step in MFMA B-operand
+ *              order: slot (c + 16*ks) holds row c, k = 64*step + 16*ks .. +15
+ *   packed_w4  [n4p/16][K/128][64][16 B] uint4 pairs; slot (c + 16*ks) holds row c of the
+ *              tile: bytes 0-7 -> k = 128*g + 16*ks .. +15, bytes 8-15 -> the same + 64;
+ *              inside 8 bytes, byte b of dword d holds k-local 8d+b (low nibble) and
+ *              8d+4+b (high nibble)
+ *   scales4    fp16 [n4p][ngp]           zeros4   uint4 pairs [n4p][ngp/2]
+ *   scales8    fp16 [n8p] (w8_group = K) or fp16 [n8p][ngp] (w8_group = 128)
+ *   feature_perm int32 [N]: row j of the concatenation [8-bit rows ; 4-bit rows] is
+ *              output channel feature_perm[j]; a bijection on [0,N)
+ *   xq int8 [M][K] row-major     xscale fp16 [M][K/act_group]     y fp16 [M][N]
+ */
+typedef struct mixllm_sizes {
+    size_t w8_bytes, w4_bytes, scales8_bytes, scales4_bytes, zeros4_bytes, perm_bytes;
+    size_t xq_bytes, xscale_bytes, y_bytes;
+    size_t workspace_bytes;   /* scratch for mixllm_mixed_linear; currently always 0 */
+} mixllm_sizes;
+
+const char *mixllm_status_string(int status);
+
+/* Library/ABI version, bumped when a packed layout or a signature changes. */
+int mixllm_abi_version(void);
+
+/* Pure host arithmetic; never touches the GPU.  Errors: EINVAL (null), EUNSUPPORTED (dims). */
+int mixllm_query_sizes(const mixllm_desc *d, mixllm_sizes *out);
+
+/*
+ * Order of the concatenated rows (Sec. 3.4: the two parts own different channel indices):
+ * the n8 salient channels ascending, then all other channels ascending.  HOST pointers
+ * in and out; pure host code.  salient_idx may be in any order.
+ * Errors: EINVAL for null pointers, an index outside [0,N) or a duplicate.
+ */
+int mixllm_build_feature_perm(int32_t N, int32_t n8, const int32_t *salient_idx_host,
+                              int32_t *perm_host /* [N] */);
+
+/*
+ * Offline weight quantization and packing (Sec. 2 quantizer; configuration of Sec. 3.1.2 and
+ * Sec. 4.1; ahead-of-time layout prepacking, Sec. 3.3 last paragraph).
+ *   W            fp16 [N][K] row-major, device
+ *   salient_idx  HOST int32 [n8]: the channels to keep at 8 bits (the per-layer slice of
+ *                the global search result, Alg. 1; choosing them is the caller's business)
+ * 8-bit rows: s = fp16(absmax/127) per channel (or per group), q = clamp(rne(w/s),-127,127).
+ * 4-bit rows, per group of 128: mn = min(w,0), mx = max(w,0), s = fp16((mx-mn)/15),
+ * z = clamp(rne(-mn/s),0,15), q = clamp(rne(w/s)+z,0,15).  A scale that comes out 0 is
+ * stored as 1.  All in fp32 with true division and round-half-to-even.
+ * Writes packed_w8, packed_w4, scales8, scales4, zeros4, feature_perm (all device).
+ * SYNCHRONIZES: feature_perm is built on the host and copied with a blocking copy before
+ * the kernels are enqueued on `stream`.
+ */
+int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *salient_idx_host,
+                            void *packed_w8, void *packed_w4, void *scales8, void *scales4,
+                            void *zeros4, int32_t *feature_perm, void *stream);
+
+/*
+ * Canonical <-> packed conversion, so that callers (and tests) can inject codes produced
+ * elsewhere and read the library's codes back.  Canonical device arrays:
+ *   q8 int8 [n8][K]; s8 fp16 [n8][K/w8_group]; q4 uint8 [n4][K] one code (0..15) per byte;
+ *   s4 fp16 [n4][K/128]; z4 uint8 [n4][K/128] one zero point (0..15) per byte;
+ *   perm int32 [N] as above.  Arrays of an empty part may be NULL.
+ * pack copies perm to feature_perm; unpack copies it back.  Code values above 15 are
+ * masked to 4 bits.  Asynchronous on `stream`.
+ */
+int mixllm_pack_weights(const mixllm_desc *d, const int8_t *q8, const void *s8, const uint8_t *q4,
+                        const void *s4, const uint8_t *z4, const int32_t *perm, void *packed_w8,
+                        void *packed_w4, void *scales8, void *scales4, void *zeros4,
+                        int32_t *feature_perm, void *stream);
+int mixllm_unpack_weights(const mixllm_desc *d, const void *packed_w8, const void *packed_w4,
+                          const void *scales8, const void *scales4, const void *zeros4,
+                          const int32_t *feature_perm, int8_t *q8, void *s8, uint8_t *q4, void *s4,
+                          uint8_t *z4, int32_t *perm, void *stream);
+
+/*
+ * Activation quantizer (Sec. 2 formula with z = 0; 8-bit symmetric, Sec. 3.1.2):
+ * per token (or per token and group): s = fp16(absmax/127), 0 -> 1;
+ * xq = clamp(rne(x/s), -127, 127), computed in fp32 with true division.
+ *   x fp16 [M][K] -> xq int8 [M][K], xscale fp16 [M][K/act_group].  M = 0 is a no-op.
+ */
+int mixllm_quantize_activations(const mixllm_desc *d, const void *x, int8_t *xq, void *xscale,
+                                void *stream);
+
+/*
+ * The quantized linear (Fig. 1; Sec. 3.3 two-step dequantization; Sec. 3.4 scatter):
+ *   P[m,j,g]  = sum_{k in group g} xq[m,k] * (q4[j,k] - z[j,g])   (int32, exact; 8-bit rows: q8)
+ *   y[m, feature_perm[j]] = fp16( sum_g float(P[m,j,g]) * s_w[j,g] * s_a[m,g] )   (fp32 sums)
+ * One launch covers both parts.  M = 0 is a no-op.  workspace may be NULL when
+ * workspace_bytes (from mixllm_query_sizes) is 0.
+ * Errors: EINVAL, EUNSUPPORTED (path cannot run this shape, e.g. DECODE with M > 16),
+ * EWORKSPACE, EHIP.
+ */
+int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xscale,
+                        const void *packed_w4, const void *packed_w8, const void *scales4,
+                        const void *scales8, const void *zeros4, const int32_t *feature_perm,
+                        void *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Same, with the kernel chosen by the caller (MIXLLM_PATH_*); for tests and benchmarks. */
+int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void *xscale,
+                             const void *packed_w4, const void *packed_w8, const void *scales4,
+                             const void *scales8, const void *zeros4, const int32_t *feature_perm,
+                             void *y, void *workspace, size_t workspace_bytes, int path,
+                             void *stream);
+
+/*
+ * Test hook: the exact int32 partial sum of every (token, channel, group), produced by the
+ * integer pipeline of the chosen path (same loads, unpacking and MFMA sequence as the
+ * linear), written in ORIGINAL channel order:  P int32 [M][N][K/128].
+ */
+int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const void *packed_w4,
+                                const void *packed_w8, const void *zeros4,
+                                const int32_t *feature_perm, int32_t *P, int path, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXLLM_H */

@@ -1,0 +1,254 @@
+// C ABI of libmixllm_hip.so: argument validation (host only, before anything is launched),
+// size accounting, feature permutation, and dispatch to the kernel launchers.
+#include <vector>
+
+#include "internal.h"
+
+using namespace mixllm;
+
+namespace {
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// A buffer argument: must be non-null and 16-byte aligned when its size is non-zero.
+inline bool buf_ok(const void *p, size_t bytes) { return bytes == 0 || (p != nullptr && aligned16(p)); }
+
+int check_desc(const mixllm_desc *d)
+{
+    if (!d) return MIXLLM_EINVAL;
+    if (d->M < 0 || d->K <= 0 || d->N <= 0 || d->n8 < 0 || d->n8 > d->N) return MIXLLM_EINVAL;
+    if (d->group != G || d->K % G != 0) return MIXLLM_EUNSUPPORTED;
+    if (d->act_group != d->K && d->act_group != G) return MIXLLM_EUNSUPPORTED;
+    if (d->w8_group != d->K && d->w8_group != G) return MIXLLM_EUNSUPPORTED;
+    if (d->K > (1 << 20) || d->N > (1 << 24) || d->M > (1 << 24)) return MIXLLM_EUNSUPPORTED;
+    return MIXLLM_OK;
+}
+
+void sizes_of(const mixllm_desc &d, mixllm_sizes &s)
+{
+    const size_t n4 = (size_t)(d.N - d.n8);
+    const size_t n8p = (size_t)round_up(d.n8, TILE_N), n4p = (size_t)round_up((int)n4, TILE_N);
+    const size_t ng = (size_t)d.K / G, ngp = (size_t)round_up((int)ng, 8);
+    s.w8_bytes = n8p * (size_t)d.K;
+    s.w4_bytes = n4p * (size_t)d.K / 2;
+    s.scales8_bytes = (d.w8_group == d.K ? n8p : n8p * ngp) * 2;
+    s.scales4_bytes = n4p * ngp * 2;
+    s.zeros4_bytes = n4p * ngp / 2;
+    s.perm_bytes = (size_t)d.N * 4;
+    s.xq_bytes = (size_t)d.M * (size_t)d.K;
+    s.xscale_bytes = (size_t)d.M * (size_t)(d.K / d.act_group) * 2;
+    s.y_bytes = (size_t)d.M * (size_t)d.N * 2;
+    s.workspace_bytes = 0;
+}
+
+LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xscale, const void *w4,
+                         const void *w8, const void *s4, const void *s8, const void *z4,
+                         const int32_t *perm)
+{
+    LinearParams p{};
+    p.M = d.M;
+    p.K = d.K;
+    p.N = d.N;
+    p.n8 = d.n8;
+    p.n4 = d.N - d.n8;
+    p.ng = d.K / G;
+    p.ngp = round_up(p.ng, 8);
+    p.ntiles8 = round_up(p.n8, TILE_N) / TILE_N;
+    p.ntiles4 = round_up(p.n4, TILE_N) / TILE_N;
+    p.act_per_token = d.act_group == d.K ? 1 : 0;
+    p.w8_per_channel = d.w8_group == d.K ? 1 : 0;
+    p.xq = xq;
+    p.xscale = (const half_t *)xscale;
+    p.w4 = (const uint8_t *)w4;
+    p.w8 = (const int8_t *)w8;
+    p.s4 = (const half_t *)s4;
+    p.s8 = (const half_t *)s8;
+    p.z4 = (const uint8_t *)z4;
+    p.perm = perm;
+    return p;
+}
+
+int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
+
+int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t st)
+{
+    if (path == MIXLLM_PATH_AUTO) path = d.M <= 16 ? MIXLLM_PATH_DECODE : MIXLLM_PATH_PREFILL;
+    switch (path) {
+    case MIXLLM_PATH_GENERIC:
+        if (d.M > 65535) return MIXLLM_EUNSUPPORTED;
+        return hip_status(launch_linear_generic(p, st));
+    case MIXLLM_PATH_DECODE:
+        if (d.M > 16) return MIXLLM_EUNSUPPORTED;
+        return hip_status(launch_linear_decode(p, st));
+    case MIXLLM_PATH_PREFILL:
+        return hip_status(launch_linear_prefill(p, st));
+    default:
+        return MIXLLM_EINVAL;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mixllm_status_string(int status)
+{
+    switch (status) {
+    case MIXLLM_OK: return "ok";
+    case MIXLLM_EINVAL: return "invalid argument (null or misaligned pointer, bad size or index)";
+    case MIXLLM_EUNSUPPORTED: return "unsupported shape or variant";
+    case MIXLLM_EWORKSPACE: return "workspace too small";
+    case MIXLLM_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int mixllm_abi_version(void) { return 1; }
+
+int mixllm_query_sizes(const mixllm_desc *d, mixllm_sizes *out)
+{
+    if (!out) return MIXLLM_EINVAL;
+    if (int rc = check_desc(d)) return rc;
+    sizes_of(*d, *out);
+    return MIXLLM_OK;
+}
+
+int mixllm_build_feature_perm(int32_t N, int32_t n8, const int32_t *salient_idx_host, int32_t *perm_host)
+{
+    if (N <= 0 || n8 < 0 || n8 > N || !perm_host || (n8 > 0 && !salient_idx_host)) return MIXLLM_EINVAL;
+    std::vector<uint8_t> is8((size_t)N, 0);
+    for (int32_t i = 0; i < n8; ++i) {
+        const int32_t c = salient_idx_host[i];
+        if (c < 0 || c >= N || is8[c]) return MIXLLM_EINVAL;
+        is8[c] = 1;
+    }
+    int32_t a = 0, b = n8;
+    for (int32_t c = 0; c < N; ++c) perm_host[is8[c] ? a++ : b++] = c;
+    return MIXLLM_OK;
+}
+
+int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *salient_idx_host,
+                            void *packed_w8, void *packed_w4, void *scales8, void *scales4, void *zeros4,
+                            int32_t *feature_perm, void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    mixllm_sizes s;
+    sizes_of(*d, s);
+    if (!W || !aligned16(W) || !feature_perm || !aligned16(feature_perm)) return MIXLLM_EINVAL;
+    if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(scales8, s.scales8_bytes) ||
+        !buf_ok(scales4, s.scales4_bytes) || !buf_ok(zeros4, s.zeros4_bytes))
+        return MIXLLM_EINVAL;
+    std::vector<int32_t> perm((size_t)d->N);
+    if (int rc = mixllm_build_feature_perm(d->N, d->n8, salient_idx_host, perm.data())) return rc;
+    if (hipMemcpy(feature_perm, perm.data(), s.perm_bytes, hipMemcpyHostToDevice) != hipSuccess)
+        return MIXLLM_EHIP;
+    return hip_status(launch_quantize_weights(*d, W, packed_w8, packed_w4, scales8, scales4, zeros4,
+                                              feature_perm, (hipStream_t)stream));
+}
+
+int mixllm_pack_weights(const mixllm_desc *d, const int8_t *q8, const void *s8, const uint8_t *q4,
+                        const void *s4, const uint8_t *z4, const int32_t *perm, void *packed_w8,
+                        void *packed_w4, void *scales8, void *scales4, void *zeros4, int32_t *feature_perm,
+                        void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    mixllm_sizes s;
+    sizes_of(*d, s);
+    const bool has8 = d->n8 > 0, has4 = d->n8 < d->N;
+    if (!perm || !feature_perm) return MIXLLM_EINVAL;
+    if (has8 && (!q8 || !s8 || !aligned16(q8))) return MIXLLM_EINVAL;
+    if (has4 && (!q4 || !s4 || !z4)) return MIXLLM_EINVAL;
+    if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(scales8, s.scales8_bytes) ||
+        !buf_ok(scales4, s.scales4_bytes) || !buf_ok(zeros4, s.zeros4_bytes))
+        return MIXLLM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (perm != feature_perm &&
+        hipMemcpyAsync(feature_perm, perm, s.perm_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return MIXLLM_EHIP;
+    return hip_status(launch_pack_weights(*d, q8, s8, q4, s4, z4, packed_w8, packed_w4, scales8, scales4,
+                                          zeros4, st));
+}
+
+int mixllm_unpack_weights(const mixllm_desc *d, const void *packed_w8, const void *packed_w4,
+                          const void *scales8, const void *scales4, const void *zeros4,
+                          const int32_t *feature_perm, int8_t *q8, void *s8, uint8_t *q4, void *s4,
+                          uint8_t *z4, int32_t *perm, void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    mixllm_sizes s;
+    sizes_of(*d, s);
+    const bool has8 = d->n8 > 0, has4 = d->n8 < d->N;
+    if (!perm || !feature_perm) return MIXLLM_EINVAL;
+    if (has8 && (!q8 || !s8 || !aligned16(q8))) return MIXLLM_EINVAL;
+    if (has4 && (!q4 || !s4 || !z4)) return MIXLLM_EINVAL;
+    if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(scales8, s.scales8_bytes) ||
+        !buf_ok(scales4, s.scales4_bytes) || !buf_ok(zeros4, s.zeros4_bytes))
+        return MIXLLM_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (perm != feature_perm &&
+        hipMemcpyAsync(perm, feature_perm, s.perm_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return MIXLLM_EHIP;
+    return hip_status(launch_unpack_weights(*d, packed_w8, packed_w4, scales8, scales4, zeros4, q8, s8, q4,
+                                            s4, z4, st));
+}
+
+int mixllm_quantize_activations(const mixllm_desc *d, const void *x, int8_t *xq, void *xscale, void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    if (d->M == 0) return MIXLLM_OK;
+    if (!x || !xq || !xscale || !aligned16(x) || !aligned16(xq) || !aligned16(xscale)) return MIXLLM_EINVAL;
+    return hip_status(launch_quantize_activations(*d, x, xq, xscale, (hipStream_t)stream));
+}
+
+static int linear_common(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
+                         const void *packed_w8, const void *scales4, const void *scales8,
+                         const void *zeros4, const int32_t *feature_perm, void *y, int32_t *P, int path,
+                         void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_PREFILL) return MIXLLM_EINVAL;
+    if (d->M == 0) return MIXLLM_OK;
+    mixllm_sizes s;
+    sizes_of(*d, s);
+    if (!xq || !aligned16(xq) || !feature_perm || !aligned16(feature_perm)) return MIXLLM_EINVAL;
+    if (!P && (!xscale || !aligned16(xscale) || !y || !aligned16(y))) return MIXLLM_EINVAL;
+    if (P && !aligned16(P)) return MIXLLM_EINVAL;
+    if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(zeros4, s.zeros4_bytes))
+        return MIXLLM_EINVAL;
+    if (!P && (!buf_ok(scales8, s.scales8_bytes) || !buf_ok(scales4, s.scales4_bytes))) return MIXLLM_EINVAL;
+    LinearParams p = make_params(*d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm);
+    p.y = (half_t *)y;
+    p.P = P;
+    return dispatch(*d, p, path, (hipStream_t)stream);
+}
+
+int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void *xscale,
+                             const void *packed_w4, const void *packed_w8, const void *scales4,
+                             const void *scales8, const void *zeros4, const int32_t *feature_perm, void *y,
+                             void *workspace, size_t workspace_bytes, int path, void *stream)
+{
+    (void)workspace;   // no path needs scratch memory: mixllm_query_sizes reports 0
+    (void)workspace_bytes;
+    return linear_common(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, y,
+                         nullptr, path, stream);
+}
+
+int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
+                        const void *packed_w8, const void *scales4, const void *scales8, const void *zeros4,
+                        const int32_t *feature_perm, void *y, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    return mixllm_mixed_linear_path(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4,
+                                    feature_perm, y, workspace, workspace_bytes, MIXLLM_PATH_AUTO, stream);
+}
+
+int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const void *packed_w4,
+                                const void *packed_w8, const void *zeros4, const int32_t *feature_perm,
+                                int32_t *P, int path, void *stream)
+{
+    if (!P) return MIXLLM_EINVAL;
+    return linear_common(d, xq, nullptr, packed_w4, packed_w8, nullptr, nullptr, zeros4, feature_perm,
+                         nullptr, P, path, stream);
+}
+
+}  // extern "C"

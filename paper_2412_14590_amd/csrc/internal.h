@@ -1,0 +1,97 @@
+// Internal declarations shared by the HIP translation units of libmixllm_hip.so.
+// Not part of the public ABI (that is include/mixllm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mixllm.h"
+
+namespace mixllm {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 half_t;
+
+constexpr int G = MIXLLM_GROUP;   // quantization group along K (Sec. 4.1)
+constexpr int TILE_N = 16;        // rows of one packed weight tile
+
+static inline __host__ __device__ int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+// Everything a linear / partials kernel needs, by value.
+struct LinearParams {
+    int M, K, N, n8, n4;
+    int ng;         // K / 128
+    int ngp;        // ng rounded up to 8: row stride of scales4 / per-group scales8 (elements)
+    int ntiles8;    // n8p / 16
+    int ntiles4;    // n4p / 16
+    int act_per_token;   // 1: xscale [M], 0: xscale [M][ng]
+    int w8_per_channel;  // 1: scales8 [n8p], 0: scales8 [n8p][ngp]
+    const int8_t *xq;
+    const half_t *xscale;
+    const uint8_t *w4;
+    const int8_t *w8;
+    const half_t *s4;
+    const half_t *s8;
+    const uint8_t *z4;
+    const int32_t *perm;
+    half_t *y;        // linear output, or
+    int32_t *P;       // partials output (debug entry point); exactly one of y / P is used
+};
+
+// ---- packed-layout addressing (see mixllm.h for the layout description) ----
+
+// byte offset of the 16-byte slot holding row `r` (of the 4-bit part), group g, k-slot ks
+static inline __host__ __device__ size_t w4_slot_offset(int r, int g, int ks, int ng)
+{
+    return (((size_t)(r / TILE_N) * ng + g) * 64 + (r % TILE_N) + 16 * ks) * 16;
+}
+// byte offset of the 16-byte slot holding row r (of the 8-bit part), k = 64*step + 16*ks..+15
+static inline __host__ __device__ size_t w8_slot_offset(int r, int step, int ks, int nsteps)
+{
+    return (((size_t)(r / TILE_N) * nsteps + step) * 64 + (r % TILE_N) + 16 * ks) * 16;
+}
+
+// zero point of (row r, group g) from the nibble-packed array
+static inline __device__ int z4_load(const uint8_t *z4, int r, int g, int ngp)
+{
+    uint8_t b = z4[(size_t)r * (ngp / 2) + (g >> 1)];
+    return (g & 1) ? (b >> 4) : (b & 15);
+}
+
+// Unpack one dword of 8 uint4 codes into two dwords of 4 int8 each, subtracting the zero
+// point on the way (step 1 of the two-step dequantization, Sec. 3.3).  `zb` holds
+// (0x80 - z) in every byte: code + (0x80 - z) never carries between bytes (<= 0x8F), and
+// flipping the top bit of each byte afterwards leaves code - z in two's complement.
+static inline __device__ void unpack_sub(uint32_t w, uint32_t zb, int &lo, int &hi)
+{
+    lo = (int)(((w & 0x0F0F0F0Fu) + zb) ^ 0x80808080u);
+    hi = (int)((((w >> 4) & 0x0F0F0F0Fu) + zb) ^ 0x80808080u);
+}
+// 16 codes (two packed dwords) -> the four int8 dwords one lane feeds to an MFMA, k order 0..15
+static inline __device__ v4i unpack16(uint32_t w0, uint32_t w1, uint32_t zb)
+{
+    int a, b, c, d;
+    unpack_sub(w0, zb, a, b);
+    unpack_sub(w1, zb, c, d);
+    return v4i{a, b, c, d};
+}
+static inline __device__ uint32_t zbias(int z) { return 0x80808080u - 0x01010101u * (uint32_t)z; }
+
+// ---- launchers (defined one per .hip file); return a hipError_t as int ----
+int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq, void *xs,
+                                hipStream_t st);
+int launch_quantize_weights(const mixllm_desc &d, const void *W, void *w8, void *w4, void *s8,
+                            void *s4, void *z4, const int32_t *perm, hipStream_t st);
+int launch_pack_weights(const mixllm_desc &d, const int8_t *q8, const void *s8c, const uint8_t *q4,
+                        const void *s4c, const uint8_t *z4c, void *w8, void *w4, void *s8,
+                        void *s4, void *z4, hipStream_t st);
+int launch_unpack_weights(const mixllm_desc &d, const void *w8, const void *w4, const void *s8,
+                          const void *s4, const void *z4, int8_t *q8, void *s8c, uint8_t *q4,
+                          void *s4c, uint8_t *z4c, hipStream_t st);
+int launch_linear_generic(const LinearParams &p, hipStream_t st);
+int launch_linear_decode(const LinearParams &p, hipStream_t st);
+int launch_linear_prefill(const LinearParams &p, hipStream_t st);
+
+}  // namespace mixllm

@@ -1,0 +1,98 @@
+// Activation quantizer: fp16 -> int8 symmetric, one scale per token or per (token, group).
+// Sec. 2 quantizer formula with z = 0; 8-bit symmetric activations, Sec. 3.1.2.
+// HBM-streaming kernel: 2 B read + 1 B written per element.
+#include "internal.h"
+
+namespace mixllm {
+
+typedef half_t h8 __attribute__((ext_vector_type(8)));
+
+static __device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// fp32 scale -> stored fp16 scale; a scale that is (or rounds to) zero becomes 1.
+static __device__ inline half_t store_scale(float s32)
+{
+    half_t s16 = (half_t)s32;   // round-to-nearest-even conversion
+    if ((float)s16 == 0.0f) s16 = (half_t)1.0f;
+    return s16;
+}
+
+static __device__ inline uint2 quant8(const h8 &v, float s)
+{
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float t = __builtin_rintf((float)v[i] / s);        // IEEE division, ties to even
+        t = fminf(fmaxf(t, -127.0f), 127.0f);
+        w[i >> 2] |= ((uint32_t)(int)t & 0xffu) << (8 * (i & 3));
+    }
+    return make_uint2(w[0], w[1]);
+}
+
+// One block per token; the row is read twice (the second read hits L2).
+__global__ __launch_bounds__(256) void act_quant_per_token(const half_t *__restrict__ x,
+                                                           int8_t *__restrict__ xq,
+                                                           half_t *__restrict__ xs, int K)
+{
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    const h8 *row = (const h8 *)(x + (size_t)m * K);
+    const int nvec = K / 8;
+    float amax = 0.0f;
+    for (int v = threadIdx.x; v < nvec; v += 256) {
+        h8 d = row[v];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)d[i]));
+    }
+    amax = wave_max(amax);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    half_t s16 = store_scale(amax / 127.0f);
+    float s = (float)s16;
+    if (threadIdx.x == 0) xs[m] = s16;
+    uint2 *out = (uint2 *)(xq + (size_t)m * K);
+    for (int v = threadIdx.x; v < nvec; v += 256) out[v] = quant8(row[v], s);
+}
+
+// 16 lanes per quantization group of 128; a block covers 16 groups of one token.
+__global__ __launch_bounds__(256) void act_quant_per_group(const half_t *__restrict__ x,
+                                                           int8_t *__restrict__ xq,
+                                                           half_t *__restrict__ xs, int K, int ng)
+{
+    const int m = blockIdx.x;
+    const int g = blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (g >= ng) return;   // whole 16-lane groups leave together; no block barrier below
+    const size_t off = (size_t)m * K + (size_t)g * G + (threadIdx.x & 15) * 8;
+    h8 d = *(const h8 *)(x + off);
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)d[i]));
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 16));
+    half_t s16 = store_scale(amax / 127.0f);
+    if ((threadIdx.x & 15) == 0) xs[(size_t)m * ng + g] = s16;
+    *(uint2 *)(xq + off) = quant8(d, (float)s16);
+}
+
+int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq, void *xs,
+                                hipStream_t st)
+{
+    if (d.M == 0) return hipSuccess;
+    if (d.act_group == d.K) {
+        hipLaunchKernelGGL(act_quant_per_token, dim3(d.M), dim3(256), 0, st, (const half_t *)x, xq,
+                           (half_t *)xs, d.K);
+    } else {
+        const int ng = d.K / G;
+        hipLaunchKernelGGL(act_quant_per_group, dim3(d.M, (ng + 15) / 16), dim3(256), 0, st,
+                           (const half_t *)x, xq, (half_t *)xs, d.K, ng);
+    }
+    return (int)hipGetLastError();
+}
+
+}  // namespace mixllm

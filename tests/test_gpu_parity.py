@@ -1,0 +1,246 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle on the same
+seeded inputs.  Integer results (codes, zero points, permutations, per-group partial sums)
+must be bit-exact; fp16 outputs must agree within TOL (row-L2-normalised)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2412_14590_amd as mx
+from oracle import ref
+from paper_2412_14590_amd import synth
+
+from util import G, TOL, dev, make_case, pack_from_oracle, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+PATHS = {"generic": mx.PATH_GENERIC, "decode": mx.PATH_DECODE, "prefill": mx.PATH_PREFILL}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------- activation quantizer --
+
+@pytest.mark.parametrize("M,K", [(1, 4096), (16, 4096), (37, 512), (5, 128), (130, 14336)])
+@pytest.mark.parametrize("grouped", [False, True])
+def test_activation_quantizer_bit_exact(M, K, grouped):
+    say("act", M, K, grouped)
+    x = synth.make_x(M, K, seed=21)
+    x[0, :7] = np.float16([0.0, -0.0, 6e-8, 65504, -65504, 1e-4, 0.5])
+    if M > 2:
+        x[2] = 0                                  # a degenerate (all zero) token
+    ag = 128 if grouped else None
+    xq_ref, xs_ref = ref.quantize_act(x, ag)
+    xq, xs = mx.quantize_activations(dev(x), ag)
+    assert np.array_equal(xs.cpu().numpy().view(np.uint16), xs_ref.view(np.uint16))
+    assert np.array_equal(xq.cpu().numpy(), xq_ref)
+
+
+def test_activation_quantizer_empty_batch():
+    x = torch.empty((0, 256), dtype=torch.float16, device="cuda")
+    xq, xs = mx.quantize_activations(x)
+    assert xq.shape == (0, 256)
+
+
+# ------------------------------------------------------ weight quantizer, pack, unpack --
+
+@pytest.mark.parametrize("K,N,n8", [(256, 100, 7), (384, 33, 0), (128, 16, 16), (4096, 530, 53), (1024, 48, 17)])
+@pytest.mark.parametrize("w8_group", [None, 128])
+def test_weight_quantizer_codes_bit_exact(K, N, n8, w8_group):
+    say("wq", K, N, n8, w8_group)
+    W, sal, L, *_ = make_case(0, K, N, n8, seed=22, w8_group=w8_group)
+    W = W.copy()
+    W[N // 2, :128] = 0                                       # a degenerate group
+    L = ref.quantize_weights(W, sal, G, w8_group)
+    P = mx.quantize_weights(dev(W), sal, w8_group)
+    u = mx.unpack_weights(P)
+    assert np.array_equal(u["perm"].cpu().numpy(), L.perm)
+    if L.n8:
+        assert np.array_equal(u["s8"].cpu().numpy().view(np.uint16), L.s8.view(np.uint16))
+        assert np.array_equal(u["q8"].cpu().numpy(), L.q8)
+    if L.n4:
+        assert np.array_equal(u["s4"].cpu().numpy().view(np.uint16), L.s4.view(np.uint16))
+        assert np.array_equal(u["z4"].cpu().numpy(), L.z4)
+        assert np.array_equal(u["q4"].cpu().numpy(), L.q4)
+
+
+@pytest.mark.parametrize("K,N,n8", [(256, 100, 7), (384, 33, 33), (640, 35, 0)])
+@pytest.mark.parametrize("w8_group", [None, 128])
+def test_pack_unpack_round_trip_and_padding_is_zero(K, N, n8, w8_group):
+    _, _, L, *_ = make_case(0, K, N, n8, seed=23, w8_group=w8_group)
+    P = pack_from_oracle(L)
+    u = mx.unpack_weights(P)
+    for k in ("q8", "q4", "z4", "perm"):
+        assert np.array_equal(u[k].cpu().numpy(), getattr(L, k)), k
+    for k in ("s8", "s4"):
+        assert np.array_equal(u[k].cpu().numpy().view(np.uint16), getattr(L, k).view(np.uint16)), k
+    # packing the same codes and quantizing on the GPU give byte-identical buffers
+    # (so padding rows / groups are deterministic zeros)
+    W = make_case(0, K, N, n8, seed=23, w8_group=w8_group)[0]
+    Q = mx.quantize_weights(dev(W), L.perm[:n8], w8_group)
+    for k in ("w8", "w4", "s8", "s4", "z4", "perm"):
+        assert torch.equal(getattr(P, k), getattr(Q, k)), k
+
+
+# ------------------------------------------------------------ integer partial sums --
+
+def check_partials(M, K, N, n8, path, seed=24):
+    _, _, L, _, xq, _ = make_case(M, K, N, n8, seed)
+    P_ref = ref.group_partials(xq, L)
+    P = mx.debug_group_partials(dev(xq), pack_from_oracle(L), PATHS[path])
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), P_ref)
+
+
+@pytest.mark.parametrize("M,K,N,n8", [(3, 256, 7, 2), (16, 1024, 100, 9), (1, 4096, 300, 30), (9, 640, 50, 0),
+                                     (5, 384, 40, 40)])
+@pytest.mark.parametrize("path", ["generic", "decode"])
+def test_group_partials_bit_exact_small_m(M, K, N, n8, path):
+    say("partials", path, M, K, N, n8)
+    check_partials(M, K, N, n8, path)
+
+
+@pytest.mark.parametrize("M,K,N,n8", [(3, 256, 7, 2), (130, 512, 300, 30), (200, 1024, 530, 0), (33, 384, 70, 70),
+                                     (257, 256, 290, 29)])
+@pytest.mark.parametrize("path", ["generic", "prefill"])
+def test_group_partials_bit_exact_tiled(M, K, N, n8, path):
+    say("partials", path, M, K, N, n8)
+    check_partials(M, K, N, n8, path)
+
+
+def test_group_partials_worst_case_magnitudes():
+    # all activations +-127, weights at the code extremes: the largest partial sums the
+    # integer pipeline can see
+    K, N, n8, M = 512, 64, 16, 20
+    rng = np.random.default_rng(3)
+    xq = np.where(rng.random((M, K)) < 0.5, -127, 127).astype(np.int8)
+    perm = ref.feature_perm(N, np.arange(0, 32, 2))
+    q8 = np.where(rng.random((n8, K)) < 0.5, -127, 127).astype(np.int8)
+    q4 = np.where(rng.random((N - n8, K)) < 0.5, 0, 15).astype(np.uint8)
+    z4 = rng.integers(0, 16, (N - n8, K // G)).astype(np.uint8)
+    s8 = np.ones((n8, 1), np.float16)
+    s4 = np.ones((N - n8, K // G), np.float16)
+    L = ref.QuantizedLayer(N, K, G, K, perm, q8, s8, q4, s4, z4)
+    P_ref = ref.group_partials(xq, L)
+    assert np.abs(P_ref).max() > 1_500_000
+    PL = pack_from_oracle(L)
+    for path in ("generic", "prefill"):
+        assert np.array_equal(mx.debug_group_partials(dev(xq), PL, PATHS[path]).cpu().numpy(), P_ref), path
+    assert np.array_equal(mx.debug_group_partials(dev(xq[:16]), PL, mx.PATH_DECODE).cpu().numpy(), P_ref[:16])
+
+
+# ------------------------------------------------------------------- the linear --
+
+def check_linear(M, K, N, n8, path, variant="baseline", seed=25):
+    act_group, w8_group = (None, None) if variant == "baseline" else (128, 128)
+    _, _, L, _, xq, xs = make_case(M, K, N, n8, seed, w8_group, act_group)
+    y_ref = ref.mixed_linear(xq, xs, L)
+    y = mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), PATHS[path])
+    torch.cuda.synchronize()
+    err = row_rel_err(y.cpu().numpy(), y_ref)
+    say(f"  linear {path} {variant} M={M} K={K} N={N} n8={n8}: row rel err {err:.2e}")
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("variant", ["baseline", "paper"])
+@pytest.mark.parametrize("path", ["generic", "decode"])
+@pytest.mark.parametrize("M,K,N,n8", [(1, 4096, 4096, 410), (16, 1024, 100, 9), (4, 640, 50, 0), (7, 384, 40, 40),
+                                     (8, 14336, 272, 27)])
+def test_linear_small_m(M, K, N, n8, path, variant):
+    check_linear(M, K, N, n8, path, variant)
+
+
+@pytest.mark.parametrize("variant", ["baseline", "paper"])
+@pytest.mark.parametrize("path", ["generic", "prefill"])
+@pytest.mark.parametrize("M,K,N,n8", [(17, 256, 7, 2), (130, 512, 300, 30), (200, 1024, 530, 0), (33, 384, 70, 70),
+                                     (512, 4096, 1024, 102)])
+def test_linear_tiled(M, K, N, n8, path, variant):
+    check_linear(M, K, N, n8, path, variant)
+
+
+def test_auto_dispatch_and_end_to_end_from_fp16():
+    # x fp16 -> quantizer -> linear, everything on the GPU, weights quantized on the GPU
+    for M in (1, 16, 17, 300):
+        W, sal, L, x, xq, xs = make_case(M, 1024, 272, 27, seed=26)
+        PL = mx.quantize_weights(dev(W), sal)
+        y = mx.linear(dev(x), PL)
+        y_ref = ref.mixed_linear(xq, xs, L)
+        assert row_rel_err(y.cpu().numpy(), y_ref) <= TOL
+    with pytest.raises(mx.MixllmError):
+        mx.mixed_linear(dev(xq), dev(xs), PL, mx.PATH_DECODE)     # M = 300 > 16
+
+
+def test_empty_batch_is_a_no_op():
+    _, _, L, *_ = make_case(0, 256, 40, 4, seed=27)
+    PL = pack_from_oracle(L)
+    xq = torch.empty((0, 256), dtype=torch.int8, device="cuda")
+    xs = torch.empty((0, 1), dtype=torch.float16, device="cuda")
+    assert mx.mixed_linear(xq, xs, PL).shape == (0, 40)
+
+
+def test_output_permutation_and_determinism():
+    # permuting output features only permutes y (Sec. 3.1.1), and reruns are bit-identical
+    M, K, N = 8, 512, 96
+    W = synth.make_w(N, K, seed=28, n_outlier_rows=4)
+    sal = np.array([3, 17, 40, 41, 95], np.int32)
+    x = dev(synth.make_x(M, K, seed=28))
+    y1 = mx.linear(x, mx.quantize_weights(dev(W), sal))
+    y1b = mx.linear(x, mx.quantize_weights(dev(W), sal))
+    assert torch.equal(y1, y1b)
+    sigma = np.random.default_rng(4).permutation(N)
+    inv = np.argsort(sigma)
+    y2 = mx.linear(x, mx.quantize_weights(dev(W[sigma]), np.sort(inv[sal]).astype(np.int32)))
+    assert torch.equal(y2, y1[:, torch.from_numpy(sigma).cuda()])
+
+
+# ------------------------------------------------ full-size layers of the workloads --
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+def test_llama3_8b_decode_layers_full_size(name):
+    K, N = synth.LLAMA3_8B[name]
+    lay = synth.make_layer(name, K, N, seed=1)
+    say("8B decode", name, K, N, lay.n8)
+    L = ref.quantize_weights(lay.W, lay.salient_idx)
+    PL = mx.quantize_weights(dev(lay.W), lay.salient_idx)
+    u = mx.unpack_weights(PL)
+    assert np.array_equal(u["q4"].cpu().numpy(), L.q4) and np.array_equal(u["q8"].cpu().numpy(), L.q8)
+    assert np.array_equal(u["z4"].cpu().numpy(), L.z4)
+    for M in (1, 4, 8, 16):
+        x = synth.make_x(M, K, seed=100 + M)
+        xq_ref, xs_ref = ref.quantize_act(x)
+        xq, xs = mx.quantize_activations(dev(x))
+        assert np.array_equal(xq.cpu().numpy(), xq_ref)
+        y = mx.mixed_linear(xq, xs, PL)
+        y_ref = ref.mixed_linear(xq_ref, xs_ref, L)
+        err = row_rel_err(y.cpu().numpy(), y_ref)
+        say(f"  M={M}: row rel err {err:.2e}")
+        assert err <= TOL
+        if M == 16:
+            P = mx.debug_group_partials(xq, PL, mx.PATH_DECODE)
+            assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref, L))
+
+
+@pytest.mark.parametrize("name,M", [("o", 2048), ("qkv", 512), ("gate_up", 2048), ("down", 2048)])
+def test_llama3_8b_prefill_layers_full_size_sampled_rows(name, M):
+    # The GPU runs the whole layer in the configuration the benchmark times; the O(MNK)
+    # oracle checks a seeded sample of token rows (all N channels, all groups).
+    K, N = synth.LLAMA3_8B[name]
+    lay = synth.make_layer(name, K, N, seed=1)
+    say("8B prefill", name, M, K, N)
+    L = ref.quantize_weights(lay.W, lay.salient_idx)
+    PL = mx.quantize_weights(dev(lay.W), lay.salient_idx)
+    x = synth.make_x(M, K, seed=200)
+    xq, xs = mx.quantize_activations(dev(x))
+    y = mx.mixed_linear(xq, xs, PL)
+    rows = np.sort(np.random.default_rng(7).choice(M, 24, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    xq_ref, xs_ref = ref.quantize_act(x[rows])
+    assert np.array_equal(xq.cpu().numpy()[rows], xq_ref)
+    y_ref = ref.mixed_linear(xq_ref, xs_ref, L)
+    err = row_rel_err(y.cpu().numpy()[rows], y_ref)
+    say(f"  row rel err {err:.2e}")
+    assert err <= TOL
+    # integer pipeline of the tiled path at full N and K on those rows
+    P = mx.debug_group_partials(dev(xq_ref), PL, mx.PATH_PREFILL)
+    assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref, L))
