@@ -115,15 +115,19 @@ def test_group_partials_worst_case_magnitudes():
     K, N, n8, M = 512, 64, 16, 20
     rng = np.random.default_rng(3)
     xq = np.where(rng.random((M, K)) < 0.5, -127, 127).astype(np.int8)
+    xq[0], xq[1] = 127, -127
     perm = ref.feature_perm(N, np.arange(0, 32, 2))
     q8 = np.where(rng.random((n8, K)) < 0.5, -127, 127).astype(np.int8)
+    q8[0], q8[1] = 127, -127
     q4 = np.where(rng.random((N - n8, K)) < 0.5, 0, 15).astype(np.uint8)
     z4 = rng.integers(0, 16, (N - n8, K // G)).astype(np.uint8)
+    q4[0], z4[0] = 15, 0
+    q4[1], z4[1] = 0, 15
     s8 = np.ones((n8, 1), np.float16)
     s4 = np.ones((N - n8, K // G), np.float16)
     L = ref.QuantizedLayer(N, K, G, K, perm, q8, s8, q4, s4, z4)
     P_ref = ref.group_partials(xq, L)
-    assert np.abs(P_ref).max() > 1_500_000
+    assert P_ref.max() == 128 * 127 * 127 and P_ref.min() == -128 * 127 * 127
     PL = pack_from_oracle(L)
     for path in ("generic", "prefill"):
         assert np.array_equal(mx.debug_group_partials(dev(xq), PL, PATHS[path]).cpu().numpy(), P_ref), path
