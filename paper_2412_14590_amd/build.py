@@ -6,7 +6,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
-LIB = os.path.join(HERE, "libmixllm_hip.so")
+LIB = os.environ.get("MIXLLM_LIB_OUT", os.path.join(HERE, "libmixllm_hip.so"))
+PROBE_LIB = os.path.join(HERE, "libmixllm_probe.so")
 SOURCES = ["api.hip", "quant_act.hip", "quant_weights.hip", "linear_generic.hip",
            "linear_decode.hip", "linear_prefill.hip"]
 
@@ -15,7 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-fhip-fp32-correctly-rounded-divide-sqrt", "-ffp-contract=off",
          # no compiler-generated packed fp32 arithmetic
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-I", INCLUDE, "-I", CSRC]
+         "-Wall", "-Wno-unused-function", "-I", INCLUDE, "-I", CSRC] + os.environ.get("MIXLLM_EXTRA_FLAGS", "").split()
 
 
 def _hipcc():
@@ -53,6 +54,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    # the ceiling probes of the benchmark: a separate small library
+    r = subprocess.run([_hipcc(), *FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, "probe.hip")],
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        print(r.stdout, file=sys.stderr)
+        raise RuntimeError("hipcc failed on probe.hip")
     return LIB
 
 

@@ -1,5 +1,6 @@
 // C ABI of libmixllm_hip.so: argument validation (host only, before anything is launched),
 // size accounting, feature permutation, and dispatch to the kernel launchers.
+#include <cstdlib>
 #include <vector>
 
 #include "internal.h"
@@ -65,6 +66,9 @@ LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xsc
     p.s8 = (const half_t *)s8;
     p.z4 = (const uint8_t *)z4;
     p.perm = perm;
+    // MIXLLM_TUNE selects an alternative launch shape inside a path (tuning experiments only)
+    static const int tune = [] { const char *e = getenv("MIXLLM_TUNE"); return e ? atoi(e) : 0; }();
+    p.tune = tune;
     return p;
 }
 

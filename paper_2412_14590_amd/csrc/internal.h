@@ -28,6 +28,7 @@ struct LinearParams {
     int ntiles4;    // n4p / 16
     int act_per_token;   // 1: xscale [M], 0: xscale [M][ng]
     int w8_per_channel;  // 1: scales8 [n8p], 0: scales8 [n8p][ngp]
+    int tune;            // launch-shape override for experiments (0 = library default)
     const int8_t *xq;
     const half_t *xscale;
     const uint8_t *w4;
