@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--workload", choices=["decode", "prefill"], default="decode")
     ap.add_argument("--m", type=int, default=None, help="tokens (default 1 for decode, 2048 for prefill)")
     ap.add_argument("--no-extras", action="store_true", help="primary leg only (for profiling)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch a plain 1 GiB copy kernel (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -94,7 +97,40 @@ def main():
             mx.mixed_linear(xq, xsc, ws[li], out=y)
 
     def time_steps(M, steps, warmup):
+        """Seconds per step.  Decode steps are launch bound when driven from Python (8 ctypes
+        calls of ~5 us each), so n_copies consecutive steps (one per weight copy) are captured
+        into one HIP graph and replayed; the graph's output is checked against eager once."""
         xs_, bufs = make_acts(M)
+        use_graph = not args.no_graph and M <= 16
+        for i in range(max(warmup, n_copies) if not use_graph else n_copies):
+            step(i, xs_, bufs)
+        torch.cuda.synchronize()
+        if use_graph:
+            eager = [b[2].clone() for b in bufs]          # y of the last eager step (copy n_copies - 1)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    for i in range(n_copies):
+                        step(i, xs_, bufs)
+            torch.cuda.current_stream().wait_stream(side)
+            for rep in range(3):                          # replay check, with eager work in between
+                for b in bufs:
+                    b[2].zero_()
+                graph.replay()
+                torch.cuda.synchronize()
+                for e, b in zip(eager, bufs):
+                    assert torch.equal(e, b[2]), "HIP graph replay differs from eager launch"
+            nrep_w, nrep = max(1, warmup // n_copies), max(1, -(-steps // n_copies))
+            for _ in range(nrep_w):
+                graph.replay()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(nrep):
+                graph.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / (nrep * n_copies)
         for i in range(warmup):
             step(i, xs_, bufs)
         torch.cuda.synchronize()
@@ -159,7 +195,14 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": primary["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # HBM bytes per launch of that kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+    # same command (scaled by a plain copy of known size); measured offline, kept under profiles/
     roof["traffic"] = None
+    tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        key = ("decode" if decode_like else "prefill") + f"_m{M0}_{l.name}"
+        roof["traffic"] = json.load(open(tpath)).get(key)
+    roof["algorithmic"] = layer_alg_bytes(l.K, l.N, l.n8, M0) if decode_like else 2.0 * M0 * l.K * l.N
     roof["kernel"] = f"mixed_linear {'decode' if decode_like else 'prefill'} path, layer {l.name} K={l.K} N={l.N} M={M0}"
     roof["us_per_launch"] = primary["dominant_kernel"]["us_event_mean"]
 
@@ -177,6 +220,22 @@ def main():
         "step_GBps": primary["GBps"], "step_TOPS": primary["TOPS"],
         "roofline": roof,
     }
+
+    # ---- measured ceilings of this GPU (context for the published peaks) ----------------------
+    if not args.no_extras:
+        from paper_2412_14590_amd import probe
+        result["measured_ceilings"] = {"hbm_read_GBps_4GiB": probe.hbm_read_gbs(),
+                                       "mfma_int8_TOPS_register_resident": probe.mfma_int8_tops(4)}
+        log(f"[bench] measured ceilings: {result['measured_ceilings']}")
+    if args.copy_probe:
+        from paper_2412_14590_amd import probe
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        a.fill_(1)
+        for _ in range(3):
+            probe.copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---- extra legs ------------------------------------------------------------------------
     if not args.no_extras:
