@@ -1,33 +1,107 @@
-// Prefill path of the quantized linear (M > 16 tokens): int8-MFMA bound.
+// Prefill path of the quantized linear (M > 16 tokens): int8-MFMA bound, with the vector
+// ALU (unpack + float rescale) as the ceiling right beneath it.
 //
-// A block of WM x WN waves computes a (WM*TM*32) x (WN*TN*32) tile of y with
-// v_mfma_i32_32x32x32_i8; a wave owns TM x TN MFMA tiles of 32 tokens x 32 channels.
-//  * Activations (A operand, rows = tokens) are staged per quantization group through LDS,
-//    double buffered, one barrier per group; rows are padded to 144 bytes so that the
-//    16-byte fragment reads of 32 lanes fall in distinct banks.
-//  * Packed weights (B operand, columns = channels) go HBM/L2 -> registers directly, in the
-//    same packed layout the decode path streams: two 16-byte loads per lane fetch one group
-//    of one 32-channel tile.  No weight byte passes through LDS.
+// A block of WM x WN waves computes a (WM*TM*32) x (WN*32) tile of y with
+// v_mfma_i32_32x32x32_i8; a wave owns TM token tiles of 32 x 32 for one 32-channel tile.
+//  * Activations (A operand, rows = tokens) go HBM/L2 -> LDS directly (16-byte
+//    global_load_lds, no registers), one quantization group (128 k) per stage, four stages.
+//    Rows are 128 bytes; the 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7),
+//    so that the fragment reads of 16 consecutive lanes cover all 64 banks exactly once.
+//  * Packed weights (B operand, columns = channels) go L2 -> registers directly in the same
+//    packed layout the decode path streams: two 16-byte loads per lane fetch one group of a
+//    32-channel tile.  No weight byte passes through LDS.
 //  * uint4 -> int8 unpack with zero-point subtraction in registers (step 1 of the two-step
-//    dequantization, Sec. 3.3), once per group, reused by the TM token tiles of the wave.
-//  * Per group and tile: 4 chained MFMAs (K = 128) into an int32 accumulator, then
-//    int->float and one FMA per element with the group scale (step 2, Sec. 3.3).  The
+//    dequantization, Sec. 3.3), once per group per wave, reused by the TM token tiles; the
+//    unpack of group g+1 is spread over the second half of group g's MFMAs.
+//  * Per group and tile: 4 chained MFMAs (K = 128) from a literal-zero accumulator into int32,
+//    then int->float and one FMA per element with the group scale (step 2, Sec. 3.3).  The
 //    channel a lane owns is the MFMA column, so the group scale is one register per lane.
-//  * Issue order.  On this hardware a vector instruction only overlaps an MFMA that does
-//    not feed the next MFMA in program order, and a dependent MFMA issued right behind its
-//    predecessor stalls the port.  So tiles are processed in pairs (two independent
-//    accumulation chains, alternating), and the float rescale of the PREVIOUS pair (and the
-//    LDS reads of the next fragments) is placed in the shadow of each MFMA; the pipeline
-//    runs across group boundaries.  Two waves per SIMD cover the remaining bubbles.
+//  * Issue order.  A group is TM*4 MFMA slots.  Tiles are processed in pairs (two independent
+//    accumulation chains, alternating); the float rescale of the PREVIOUS pair runs in the
+//    shadow of the current pair's MFMAs (8 vector instructions per MFMA is what the vector port
+//    sustains at full MFMA rate), and the A fragment of slot s+6 is requested at slot s (LDS
+//    latency is several MFMAs long).  The pipeline runs across group boundaries; the only
+//    block-wide barrier sits in the middle of a group (slot TM*2), where the next group's
+//    activations are known to have landed and the stage of the previous group is released.
+//  * Group metadata (4 fp16 scales, 4 zero points) is fetched once per 4 groups.
 //  * Epilogue: token scale, fp16 conversion, scatter to the original channel (Sec. 3.4).
 // 8-bit and 4-bit channel tiles are different block ranges of one launch.
+#include <mutex>
 #include <type_traits>
 
 #include "internal.h"
 
 namespace mixllm {
 
-constexpr int A_STRIDE = G + 16;   // bytes per LDS row of the activation tile
+constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
+constexpr int DFRAG = 6;    // an A fragment is requested this many MFMA slots before its use
+constexpr int RING = 8;     // fragment registers (DFRAG + 2: the slot being overwritten is two MFMAs old)
+
+// ---- asynchronous global loads, issued and awaited by hand ---------------------------------
+// Inside the main loops every global load is an `asm volatile`, for two reasons.  (1) The
+// direct-to-LDS load, when the compiler sees it, makes its wait-count bookkeeping fall back to
+// waiting for ALL outstanding memory operations before any later dependent instruction, which
+// serialises the fragment pipeline.  (2) The vector-memory counter retires in order: with the
+// loads hidden in asm the issue order is exactly the program order, so one `s_waitcnt vmcnt(N)`
+// ("all but the youngest N loads of this wave have landed") per group covers everything, and
+// the youngest loads - the activation tile two groups ahead - stay in flight across it.
+// A register filled by such a load is only read after passing through await_*(), which ties
+// the register to the wait.  A wait with N smaller than the number of younger loads merely
+// waits longer; it is never unsafe.
+
+// 16 bytes per lane, global -> LDS: lane l writes lds_base + 16 l.  lds_base is wave uniform.
+static __device__ inline void load_lds16(uint32_t lds_base, uint32_t voff, const void *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+}
+template <int OFF>
+static __device__ inline void load_reg16(v4i &dst, uint32_t voff, const void *sbase)
+{
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=&v"(dst) : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
+}
+static __device__ inline void load_reg8(uint2 &dst, uint32_t voff, const void *sbase)
+{
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
+}
+static __device__ inline void load_reg_u16(uint32_t &dst, uint32_t voff, const void *sbase)
+{
+    asm volatile("global_load_ushort %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
+}
+template <int N>
+static __device__ inline void await_loads(v4i &a, v4i &b)
+{
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+template <int N>
+static __device__ inline void await_loads(v4i &a, v4i &b, v4i &c, v4i &d)
+{
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+template <int N>
+static __device__ inline void await_loads()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int N>
+static __device__ inline void await_loads(uint2 &a, uint32_t &b)
+{
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+// Block-wide barrier in the middle of a group, written out instead of __syncthreads(): the
+// fence of the latter would wait for every outstanding load and LDS read.  The caller has
+// already waited for what must have landed; LDS_WRITES adds this wave's own LDS stores.
+template <bool LDS_WRITES>
+static __device__ inline void mid_group_barrier()
+{
+    if (LDS_WRITES)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+        asm volatile("s_barrier" ::: "memory");
+}
+static __device__ inline uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
 
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
 template <int I, int N, typename F>
@@ -39,171 +113,213 @@ static __device__ inline void static_for(F &&f)
     }
 }
 
-template <int WM_, int WN_, int TM_, int TN_>
+template <int WM_, int WN_, int TM_>
 struct Shape {
-    static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
-    static constexpr int THREADS = 64 * WM * WN;
+    static constexpr int WM = WM_, WN = WN_, TM = TM_;
+    static constexpr int NW = WM * WN;
+    static constexpr int THREADS = 64 * NW;
     static constexpr int BM = WM * TM * 32;       // tokens per block
-    static constexpr int BN = WN * TN * 32;       // channels per block
-    static constexpr int A_STAGE = BM * A_STRIDE;
-    static constexpr int A_CHUNKS = BM * 8 / THREADS;   // 16-byte chunks of the A tile per thread
-    static_assert(BM * 8 % THREADS == 0, "A tile must split evenly over the threads");
-    static_assert(TN == 1 || TN == 2, "a wave owns one or two 32-channel tiles");
-    static_assert((TM * TN) % 4 == 0, "tiles are processed in an even number of pairs");
+    static constexpr int BN = WN * 32;            // channels per block
+    static constexpr int A_STAGE = BM * G;        // bytes of one LDS stage
+    static constexpr int LPW = BM / 8 / NW;       // direct-to-LDS loads (8 rows each) per wave and stage
+    static_assert(BM % (8 * NW) == 0, "A tile must split evenly over the waves");
+    static_assert(TM % 4 == 0 && (TM * 4) % RING == 0, "an even number of tile pairs per group; slots wrap the fragment ring");
+    static_assert((NSTAGE - 1) * A_STAGE + (TM * WM - 1) * 32 * G + 31 * G + 127 < 65536, "LDS offsets must fit 16 bits");
 };
 
-template <typename C, bool DUMP, bool ACT_PT, bool PART8>
-static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a,
-                                            float *lds_sa)
+// ASYNC: packed weights and metadata are fetched with the hand-issued loads above.  Only valid in a
+// kernel that keeps everything in registers: a register spilled between its load and its
+// await_loads() would be saved before the data has arrived.  (The build checks that the kernels
+// instantiated with ASYNC use no scratch memory.)  Without ASYNC they are ordinary loads, which
+// the compiler awaits itself - later than necessary, because it does not see the hand-issued
+// activation loads ahead of them in the queue, but always correctly.
+template <typename C, bool DUMP, bool ACT_PT, bool PART8, bool ASYNC>
+static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a, float *lds_sa)
 {
-    constexpr int TM = C::TM, TN = C::TN, WN = C::WN;
-    constexpr int THREADS = C::THREADS, BM = C::BM, A_STAGE = C::A_STAGE, A_CHUNKS = C::A_CHUNKS;
-    constexpr int NP = TM * TN / 2;          // tile pairs per group
-    constexpr int NA = TN == 1 ? 2 : 1;      // distinct token tiles in a pair
-    constexpr int NSTEP = NP * 4;            // (pair, 32-k step) steps per group
+    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW;
+    constexpr int NSLOT = TM * 4;            // MFMAs per group
+    constexpr int HALF = NSLOT / 2;          // slot of the barrier
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int n32 = lane & 31, h = lane >> 5;
     const int ntiles = PART8 ? p.ntiles8 : p.ntiles4;
     const int nrows = PART8 ? p.n8 : p.n4;
     const int joff = PART8 ? 0 : p.n8;
-    const int nsteps = p.K / 64;
     const int ng = p.ng;
     const int mw0 = wm * TM * 32;   // first row of this wave inside the block tile
+    const bool per_group_s8 = PART8 && !p.w8_per_channel;
 
-    // this lane's channel in each of the wave's 32-channel tiles
-    int tile16[TN], rw[TN], ch[TN];
-#pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-        const int t = t16_0 + (wn * TN + nt) * 2 + (n32 >> 4);
-        tile16[nt] = min(t, ntiles - 1);
-        rw[nt] = tile16[nt] * TILE_N + (n32 & 15);
-        ch[nt] = (t < ntiles && rw[nt] < nrows) ? p.perm[joff + rw[nt]] : -1;
-    }
+    // this lane's channel
+    const int t16 = t16_0 + wn * 2 + (n32 >> 4);
+    const int tile16 = min(t16, ntiles - 1);
+    const int rw = tile16 * TILE_N + (n32 & 15);
+    const int ch = (t16 < ntiles && rw < nrows) ? p.perm[joff + rw] : -1;
 
     // ---- loaders -------------------------------------------------------------------
-    // Activation tile of one group: BM rows x 128 bytes.  Rows past M re-read row M-1: token
-    // rows are independent, and outputs of rows >= M are never stored.
-    const int8_t *a_src[A_CHUNKS];
-    int a_dst[A_CHUNKS];
+    // Activation tile of one group, straight to LDS.  Load i of this wave fills rows
+    // 8*(wave*LPW+i) .. +7: lane l writes chunk position l&7 of row +(l>>3), which holds the
+    // global chunk (l&7) ^ ((row>>1)&7).  Rows past M re-read row M-1: token rows are
+    // independent, and outputs of rows >= M are never stored.
+    uint32_t a_voff[LPW];
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-        const int id = tid + THREADS * i, row = id >> 3, c16 = id & 7;
-        a_src[i] = p.xq + (size_t)min(m0 + row, p.M - 1) * p.K + c16 * 16;
-        a_dst[i] = row * A_STRIDE + c16 * 16;
+    for (int i = 0; i < LPW; ++i) {
+        const int row = (wave * LPW + i) * 8 + (lane >> 3);
+        const int cs = (lane & 7) ^ ((row >> 1) & 7);
+        a_voff[i] = (uint32_t)min(m0 + row, p.M - 1) * (uint32_t)p.K + cs * 16;
     }
-    // weights of one group for the wave's TN tiles.
-    //  4-bit: wq[nt][0] = 16-k chunks h and 4+h, wq[nt][1] = chunks 2+h and 6+h (packed)
-    //  8-bit: wq[nt][j] = chunk 2j+h (int8)
-    constexpr int NBQ = PART8 ? 4 : 2;
-    const uint8_t *b_src[TN];
+    const uint32_t lds_a_wave = __builtin_amdgcn_readfirstlane(lds_address(lds_a) + wave * LPW * 1024);
+    auto load_a = [&](int g, int stage) {
+        const int8_t *src = p.xq + (size_t)min(g, ng - 1) * G;
 #pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-        if (PART8)
-            b_src[nt] = (const uint8_t *)p.w8 + ((size_t)tile16[nt] * nsteps * 64 + (n32 & 15)) * 16;
-        else
-            b_src[nt] = p.w4 + ((size_t)tile16[nt] * ng * 64 + (n32 & 15) + 16 * h) * 16;
-    }
-    auto load_b = [&](int g, v4i (&wq)[TN][NBQ]) {
+        for (int i = 0; i < LPW; ++i) load_lds16(lds_a_wave + stage * A_STAGE + i * 1024, a_voff[i], src);
+    };
+    // fragment read offsets: row mw0 + 32 mt + n32, global chunk 2j + h
+    int a_rd[4];
 #pragma unroll
-        for (int nt = 0; nt < TN; ++nt) {
-            if (PART8) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int c = 2 * j + h;   // 16-k chunk: 64-k step 2g + c/4, k-slot c%4
-                    wq[nt][j] = *(const v4i *)(b_src[nt] + ((size_t)(2 * g + (c >> 2)) * 64 + 16 * (c & 3)) * 16);
-                }
+    for (int j = 0; j < 4; ++j) a_rd[j] = (mw0 + n32) * G + (((2 * j + h) ^ ((n32 >> 1) & 7)) << 4);
+
+    // weights of one group for the wave's 32-channel tile
+    //  4-bit: raw[0] = 16-k chunks h and 4+h, raw[1] = chunks 2+h and 6+h (packed nibbles)
+    //  8-bit: b[j] = chunk 2j+h (int8), loaded straight into the operand registers
+    // (byte offsets of a lane inside the weight and metadata arrays fit 32 bits: checked on the host)
+    const uint32_t b_voff = PART8 ? ((uint32_t)tile16 * (uint32_t)(p.K / 64) * 64 + (n32 & 15) + 16 * h) * 16
+                                  : ((uint32_t)tile16 * (uint32_t)ng * 64 + (n32 & 15) + 16 * h) * 16;
+    v4i b[2][4];
+    v4i raw[2][2];
+    auto load_b = [&](int g, auto setc) {
+        constexpr int set = decltype(setc)::value % 2;
+        const int gc = min(g, ng - 1);
+        if (PART8) {
+            const uint8_t *base = (const uint8_t *)p.w8 + (size_t)gc * 2048;
+            if (ASYNC) {
+                load_reg16<0>(b[set][0], b_voff, base);
+                load_reg16<512>(b[set][1], b_voff, base);
+                load_reg16<1024>(b[set][2], b_voff, base);
+                load_reg16<1536>(b[set][3], b_voff, base);
             } else {
-                const uint8_t *base = b_src[nt] + (size_t)g * 1024;
-                wq[nt][0] = *(const v4i *)base;
-                wq[nt][1] = *(const v4i *)(base + 512);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[set][j] = *(const v4i *)(base + b_voff + j * 512);
+            }
+        } else {
+            const uint8_t *base = p.w4 + (size_t)gc * 1024;
+            if (ASYNC) {
+                load_reg16<0>(raw[set][0], b_voff, base);
+                load_reg16<512>(raw[set][1], b_voff, base);
+            } else {
+                raw[set][0] = *(const v4i *)(base + b_voff);
+                raw[set][1] = *(const v4i *)(base + b_voff + 512);
             }
         }
     };
-    // Group metadata is kept as loaded (fp16 scale bits, zero-point byte) and only converted
-    // when its group is computed, so that nothing waits on a load in the iteration that
-    // issued it.
+    // metadata of 4 consecutive groups (arrays are zero padded to a multiple of 8 groups)
     struct Meta {
-        half_t sw[TN];
-        uint8_t zraw[TN];
+        uint2 s;       // 4 fp16 group scales
+        uint32_t z;    // 4 uint4 zero points in the low 16 bits
     };
-    auto load_meta = [&](int g, Meta &mt) {
-#pragma unroll
-        for (int nt = 0; nt < TN; ++nt) {
-            mt.sw[nt] = (half_t)0.0f;
-            mt.zraw[nt] = 0;
+    const uint32_t s_voff = (uint32_t)rw * (uint32_t)p.ngp * 2, z_voff = (uint32_t)rw * (uint32_t)(p.ngp / 2);
+    auto load_meta = [&](int q, Meta &mt) {
+        mt.s = make_uint2(0, 0);
+        mt.z = 0;
+        const int g0 = 4 * min(q, (ng - 1) / 4);
+        if (ASYNC) {
             if (PART8) {
-                if (!DUMP) mt.sw[nt] = p.w8_per_channel ? p.s8[rw[nt]] : p.s8[(size_t)rw[nt] * p.ngp + g];
+                if (!DUMP && per_group_s8) load_reg8(mt.s, s_voff, p.s8 + g0);
             } else {
-                if (!DUMP) mt.sw[nt] = p.s4[(size_t)rw[nt] * p.ngp + g];
-                mt.zraw[nt] = p.z4[(size_t)rw[nt] * (p.ngp / 2) + (g >> 1)];
+                if (!DUMP) load_reg8(mt.s, s_voff, p.s4 + g0);
+                load_reg_u16(mt.z, z_voff, p.z4 + g0 / 2);
+            }
+        } else {
+            if (PART8) {
+                if (!DUMP && per_group_s8) mt.s = *(const uint2 *)((const uint8_t *)(p.s8 + g0) + s_voff);
+            } else {
+                if (!DUMP) mt.s = *(const uint2 *)((const uint8_t *)(p.s4 + g0) + s_voff);
+                mt.z = *(const uint16_t *)(p.z4 + g0 / 2 + z_voff);
             }
         }
+    };
+    auto scale_of = [&](const Meta &mt, int u) -> float {
+        half_t hs[4];
+        __builtin_memcpy(hs, &mt.s, 8);
+        return (float)hs[u];
+    };
+    // one eighth of the unpack of a group: raw dword d of `set` -> two operand dwords
+    auto unpack_piece = [&](auto setc, auto dc, uint32_t zb) {
+        constexpr int set = decltype(setc)::value % 2, d = decltype(dc)::value;
+        constexpr int bj = d >> 1, e = d & 1;
+        int lo, hi;
+        unpack_sub((uint32_t)raw[set][bj & 1][(bj >> 1) * 2 + e], zb, lo, hi);
+        b[set][bj][2 * e] = lo;
+        b[set][bj][2 * e + 1] = hi;
     };
 
     v16i zero16;
 #pragma unroll
     for (int i = 0; i < 16; ++i) zero16[i] = 0;
 
-    float acc[TM][TN][16];
+    float acc[TM][16];
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < TN; ++nt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 
     // Rescale (or, for the debug entry point, dump) registers 4j..4j+3 of one finished tile:
-    // rows m0 + mw0 + 32 mt + 8 j + 4 h + {0..3}, column = this lane's channel of tile nt.
-    auto finish4 = [&](const v16i &P, auto mtc, auto ntc, auto jc, float sw, int gp) {
-        constexpr int mt = decltype(mtc)::value, nt = decltype(ntc)::value, j = decltype(jc)::value;
+    // rows m0 + mw0 + 32 mt + 8 j + 4 h + {0..3}, column = this lane's channel.
+    auto finish4 = [&](const v16i &P, auto mtc, auto jc, float sw, int gp) {
+        constexpr int mt = decltype(mtc)::value, j = decltype(jc)::value;
         if (DUMP) {
-            if (gp >= 0 && gp < ng && ch[nt] >= 0) {
+            if (gp >= 0 && gp < ng && ch >= 0) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int m = m0 + mw0 + mt * 32 + 8 * j + 4 * h + i;
-                    if (m < p.M) p.P[((size_t)m * p.N + ch[nt]) * ng + gp] = P[4 * j + i];
+                    if (m < p.M) p.P[((size_t)m * p.N + ch) * ng + gp] = P[4 * j + i];
                 }
             }
         } else if (ACT_PT) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                acc[mt][nt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw, acc[mt][nt][4 * j + i]);
+            for (int i = 0; i < 4; ++i) acc[mt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw, acc[mt][4 * j + i]);
         } else {
-            // per-(token, group) activation scales of the tile's group, staged in LDS (3 stages)
-            const v4f sa = *(const v4f *)(lds_sa + ((gp + 3) % 3) * BM + mw0 + mt * 32 + 8 * j + 4 * h);
+            // per-(token, group) activation scales of the tile's group, staged in LDS
+            const v4f sa = *(const v4f *)(lds_sa + ((gp + NSTAGE) % NSTAGE) * BM + mw0 + mt * 32 + 8 * j + 4 * h);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                acc[mt][nt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw * sa[i], acc[mt][nt][4 * j + i]);
+                acc[mt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw * sa[i], acc[mt][4 * j + i]);
         }
     };
 
     // ---- prologue ------------------------------------------------------------------
-    // Global loads run two groups ahead of the MFMAs (one group of compute is shorter than a
-    // loaded memory round trip): register sets [parity of the group].  Group g+2 is requested
-    // at the top of iteration g into the set group g just vacated; activations of group g+1
-    // move from registers to the other LDS stage at the bottom of iteration g.
-    v4i areg[2][A_CHUNKS];
-    v4i wq[2][TN][NBQ];
-    Meta meta[2];
-    float sa_reg[2] = {0.0f, 0.0f};
-    const int g1 = min(1, ng - 1);
-    load_b(0, wq[0]);
-    load_meta(0, meta[0]);
-    load_b(g1, wq[1]);
-    load_meta(g1, meta[1]);
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) areg[0][i] = *(const v4i *)a_src[i];
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) areg[1][i] = *(const v4i *)(a_src[i] + (size_t)g1 * G);
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) *(v4i *)(lds_a + a_dst[i]) = areg[0][i];
+    Meta meta_cur, meta_nxt;
+    load_meta(0, meta_cur);
+    load_b(0, std::integral_constant<int, 0>{});
+    if (!PART8) load_b(1, std::integral_constant<int, 1>{});
+    load_a(0, 0);
+    load_a(1, 1);
+    load_a(2, 2);
+    float sa_reg = 0.0f;   // activation scale of (row tid, group g+1), on its way to LDS
     if (!ACT_PT && !DUMP && tid < BM) {
+#pragma unroll
+        for (int s = 1; s < NSTAGE; ++s) lds_sa[s * BM + tid] = 0.0f;   // read (times a zero scale) before first written
         lds_sa[tid] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng];
-        sa_reg[1] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + g1];
+        sa_reg = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + min(1, ng - 1)];
     }
-    __builtin_amdgcn_s_waitcnt(0);   // nothing in flight at loop entry
+    const float sw_row = (PART8 && !DUMP && p.w8_per_channel) ? (float)p.s8[rw] : 0.0f;
+    // everything above has landed (registers and LDS)
+    await_loads<0>(meta_cur.s, meta_cur.z);
+    if (PART8) await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
+    else await_loads<0>(raw[0][0], raw[0][1], raw[1][0], raw[1][1]);
     __syncthreads();
+    meta_nxt = meta_cur;
+    if (!PART8) {
+        const uint32_t zb = zbias(meta_cur.z & 15);
+        static_for<0, 8>([&](auto dc) { unpack_piece(std::integral_constant<int, 0>{}, dc, zb); });
+    }
+    v4i af[RING];
+    // fragment of slot t of the group held in `stage`
+    auto load_frag = [&](auto stagec, auto tc) {
+        constexpr int stage = decltype(stagec)::value, t = decltype(tc)::value;
+        constexpr int mt = 2 * (t / 8) + (t & 1), j = (t % 8) / 2;
+        af[t % RING] = *(const v4i *)(lds_a + a_rd[j] + stage * A_STAGE + mt * 32 * G);
+    };
+    static_for<0, DFRAG>([&](auto tc) { load_frag(std::integral_constant<int, 0>{}, tc); });
 
     // int32 accumulators of the pair in flight (P[s]) and of the pair being rescaled (P[s^1])
     v16i P[2][2];
@@ -211,102 +327,91 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int i = 0; i < 2; ++i) P[s][i] = zero16;
-    float sw_prev[TN];   // group scale of the pair left over from the previous group
-#pragma unroll
-    for (int nt = 0; nt < TN; ++nt) sw_prev[nt] = 0.0f;
+    float sw_prev = 0.0f;   // group scale of the pair left over from the previous group
 
-    // one group; PAR = g & 1 selects the register sets and the LDS stage at compile time
-    auto group_step = [&](int g, auto parc) {
-        constexpr int PAR = decltype(parc)::value;
-        // B fragments of this group: b[nt][j] = the 16 k of chunk 2j+h as int8.  A group past
-        // the end (odd group count) gets scale 0 and contributes nothing.
-        float sw_cur[TN];
-        v4i b[TN][4];
-#pragma unroll
-        for (int nt = 0; nt < TN; ++nt) {
-            sw_cur[nt] = g < ng ? (float)meta[PAR].sw[nt] : 0.0f;
-            if (PART8) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) b[nt][j] = wq[PAR][nt][j];
-            } else {
-                const uint32_t zb = zbias(PAR ? (meta[PAR].zraw[nt] >> 4) : (meta[PAR].zraw[nt] & 15));
-                b[nt][0] = unpack16((uint32_t)wq[PAR][nt][0][0], (uint32_t)wq[PAR][nt][0][1], zb);
-                b[nt][1] = unpack16((uint32_t)wq[PAR][nt][1][0], (uint32_t)wq[PAR][nt][1][1], zb);
-                b[nt][2] = unpack16((uint32_t)wq[PAR][nt][0][2], (uint32_t)wq[PAR][nt][0][3], zb);
-                b[nt][3] = unpack16((uint32_t)wq[PAR][nt][1][2], (uint32_t)wq[PAR][nt][1][3], zb);
-            }
+    // one group; U = g & 3 selects the register sets and the LDS stage at compile time
+    auto group_step = [&](int g, auto uc) {
+        constexpr int U = decltype(uc)::value;
+        float sw_cur;
+        if (PART8 && !per_group_s8) sw_cur = g < ng ? sw_row : 0.0f;
+        else sw_cur = scale_of(meta_cur, U);   // zero for groups past the end (padding)
+        uint32_t zb_next = 0;
+        // 8-bit weights need no unpack: group g+1 is requested here, straight into the operand
+        // registers group g-1 just vacated; this group's own request (one group old, only the
+        // previous middle's activation loads are younger) has to have landed
+        if (PART8) {
+            await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
+            load_b(g + 1, std::integral_constant<int, U + 1>{});
         }
-        // request group g+2 (clamped at the end: a harmless re-read keeps the body branch-free)
-        const int gn = min(g + 2, ng - 1);
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) areg[PAR][i] = *(const v4i *)(a_src[i] + (size_t)gn * G);
-        load_b(gn, wq[PAR]);
-        load_meta(gn, meta[PAR]);
-        if (!ACT_PT && !DUMP && tid < BM) sa_reg[PAR] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + gn];
-
-        // activation fragments: af[step % 3][tile of the pair], fetched two steps ahead
-        const uint8_t *a_base = lds_a + PAR * A_STAGE + (mw0 + n32) * A_STRIDE + h * 16;
-        v4i af[3][NA];
-        auto load_af = [&](auto stc) {
-            constexpr int st = decltype(stc)::value, q = st / 4, j = st % 4;
-#pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                const int mt = (2 * q + i) / TN;
-                af[st % 3][i] = *(const v4i *)(a_base + mt * 32 * A_STRIDE + j * 32);
-            }
-        };
-        load_af(std::integral_constant<int, 0>{});
-        load_af(std::integral_constant<int, 1>{});
         __builtin_amdgcn_sched_barrier(0);
 
-        static_for<0, NSTEP>([&](auto stc) {
-            constexpr int st = decltype(stc)::value, q = st / 4, j = st % 4, s = q & 1;
-            constexpr int t0 = 2 * q, t1 = 2 * q + 1;                 // tiles of the pair in flight
-            constexpr int qp = (q + NP - 1) % NP;                     // pair being rescaled
-            constexpr int u0 = 2 * qp, u1 = 2 * qp + 1;
-            const int gp = q == 0 ? g - 1 : g;                        // ... and its group
-            if constexpr (st + 2 < NSTEP) load_af(std::integral_constant<int, st + 2>{});
-            // slot 1: first tile of the pair
-            P[s][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % 3][0], b[t0 % TN][j], j == 0 ? zero16 : P[s][0], 0, 0, 0);
-            finish4(P[s ^ 1][0], std::integral_constant<int, u0 / TN>{}, std::integral_constant<int, u0 % TN>{},
-                    std::integral_constant<int, j>{}, q == 0 ? sw_prev[u0 % TN] : sw_cur[u0 % TN], gp);
-            // slot 2: second tile of the pair
-            P[s][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % 3][NA - 1], b[t1 % TN][j], j == 0 ? zero16 : P[s][1], 0, 0, 0);
-            finish4(P[s ^ 1][1], std::integral_constant<int, u1 / TN>{}, std::integral_constant<int, u1 % TN>{},
-                    std::integral_constant<int, j>{}, q == 0 ? sw_prev[u1 % TN] : sw_cur[u1 % TN], gp);
+        static_for<0, NSLOT>([&](auto stc) {
+            constexpr int st = decltype(stc)::value, q = st / 8, j = (st % 8) / 2, i = st & 1, s = q & 1;
+            constexpr int mt = 2 * q + i;
+            constexpr int qp = (q + TM / 2 - 1) % (TM / 2);         // pair being rescaled
+            constexpr int up = 2 * qp + i;                         // ... its tile handled in this slot
+            const int gp = q == 0 ? g - 1 : g;                     // ... and its group
+            if constexpr (st == HALF) {
+                // Middle of the group.  The wait leaves at most the LPW youngest loads in flight:
+                // the direct-to-LDS loads of the previous middle (activations of group g+2), which
+                // are issued last in their batch.  Everything older has landed: this wave's part
+                // of group g+1's activations, group g+1's packed weights and the metadata.  After
+                // the barrier group g+1's activations are in LDS for every wave, and every wave is
+                // done reading the stage of group g-1, which the next request overwrites.
+                if (PART8) await_loads<LPW>();
+                else await_loads<LPW>(raw[(U + 1) % 2][0], raw[(U + 1) % 2][1]);
+                if constexpr (U == 3) await_loads<LPW>(meta_nxt.s, meta_nxt.z);
+                if (!ACT_PT && !DUMP && tid < BM) lds_sa[((U + 1) % NSTAGE) * BM + tid] = sa_reg;
+                mid_group_barrier<(!ACT_PT && !DUMP)>();
+                if constexpr (U == 1) load_meta(g / 4 + 1, meta_nxt);
+                if (!ACT_PT && !DUMP && tid < BM)
+                    sa_reg = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + min(g + 2, ng - 1)];
+                if (!PART8) load_b(g + 2, std::integral_constant<int, U + 2>{});
+                load_a(g + 3, (U + 3) % NSTAGE);
+                if (!PART8) zb_next = zbias(((U == 3 ? meta_nxt.z : meta_cur.z) >> (4 * ((U + 1) % 4))) & 15);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // request the fragment DFRAG slots ahead (second half: from the next group's stage)
+            if constexpr (st + DFRAG < NSLOT)
+                load_frag(std::integral_constant<int, U>{}, std::integral_constant<int, st + DFRAG>{});
+            else
+                load_frag(std::integral_constant<int, (U + 1) % NSTAGE>{}, std::integral_constant<int, st + DFRAG - NSLOT>{});
+            P[s][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][j], j == 0 ? zero16 : P[s][i], 0, 0, 0);
+            finish4(P[s ^ 1][i], std::integral_constant<int, up>{}, std::integral_constant<int, j>{},
+                    q == 0 ? sw_prev : sw_cur, gp);
+            if constexpr (!PART8 && st >= HALF && st < HALF + 8)
+                unpack_piece(std::integral_constant<int, U + 1>{}, std::integral_constant<int, st - HALF>{}, zb_next);
             if (!DUMP) {
-                // issue order: MFMA, the LDS reads and 8 vector instructions in its shadow, twice
+                // issue order: MFMA, the LDS read(s), the vector instructions in its shadow
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, ACT_PT ? 1 : 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, ACT_PT ? 8 : 12, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, ACT_PT ? 1 : 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, ACT_PT ? 8 : 12, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, ACT_PT ? 16 : 20, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
-
-        // activations of group g+1 (requested one iteration ago) go to the other LDS stage
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) *(v4i *)(lds_a + (PAR ^ 1) * A_STAGE + a_dst[i]) = areg[PAR ^ 1][i];
-        if (!ACT_PT && !DUMP && tid < BM) lds_sa[((g + 1) % 3) * BM + tid] = sa_reg[PAR ^ 1];
-#pragma unroll
-        for (int nt = 0; nt < TN; ++nt) sw_prev[nt] = sw_cur[nt];
-        __syncthreads();
+        sw_prev = sw_cur;
     };
-    for (int g = 0; g < ng; g += 2) {
+    for (int g = 0; g < ng; g += 4) {
         group_step(g, std::integral_constant<int, 0>{});
         group_step(g + 1, std::integral_constant<int, 1>{});
+        group_step(g + 2, std::integral_constant<int, 2>{});
+        group_step(g + 3, std::integral_constant<int, 3>{});
+        meta_cur = meta_nxt;
     }
-    const int g_last = ((ng + 1) & ~1) - 1;   // group index the pending pair belongs to (may be the phantom one)
+    const int g_last = ((ng + 3) & ~3) - 1;   // group index the pending pair belongs to (may be a phantom one)
     // the last pair of the last group is still waiting for its rescale
-    static_for<0, 4>([&](auto jc) {
-        constexpr int u0 = 2 * (NP - 1), u1 = u0 + 1, sp = (NP - 1) & 1;
-        finish4(P[sp][0], std::integral_constant<int, u0 / TN>{}, std::integral_constant<int, u0 % TN>{}, jc,
-                sw_prev[u0 % TN], g_last);
-        finish4(P[sp][1], std::integral_constant<int, u1 / TN>{}, std::integral_constant<int, u1 % TN>{}, jc,
-                sw_prev[u1 % TN], g_last);
+    static_for<0, 8>([&](auto tc) {
+        constexpr int t = decltype(tc)::value, j = t / 2, i = t & 1, qp = TM / 2 - 1;
+        finish4(P[qp & 1][i], std::integral_constant<int, 2 * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last);
     });
+    // Drain: the last requests (clamped re-reads past the end of K) are still in flight, aimed at
+    // this block's LDS and at registers nothing reads any more.  Tying those registers to the
+    // wait keeps them allocated until the data has arrived; without it they could be reused
+    // (say for an epilogue address) and then be overwritten by a late load.
+    await_loads<0>(raw[0][0], raw[0][1], raw[1][0], raw[1][1]);
+    await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
+    await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
+    await_loads<0>(meta_nxt.s, meta_nxt.z);
     if (DUMP) return;
 
     // ---- epilogue: token scale, fp16, scatter (Sec. 3.4) ------------------------------
@@ -323,32 +428,213 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-#pragma unroll
-            for (int nt = 0; nt < TN; ++nt)
-                if (m < p.M && ch[nt] >= 0)
-                    p.y[(size_t)m * p.N + ch[nt]] = (half_t)(acc[mt][nt][r] * sa[r]);
+            if (m < p.M && ch >= 0) p.y[(size_t)m * p.N + ch] = (half_t)(acc[mt][r] * sa[r]);
         }
     }
 }
 
-template <typename C, int MINW, bool DUMP, bool ACT_PT>
-__global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm, int nb8,
-                                                                         int nb4, int per_xcd)
+
+// 8-bit channel tiles whose scale does not depend on the group (one scale per channel): the
+// group partial sums need no float rescale in between, so the MFMA accumulators simply run
+// over all of K in int32 (|sum| <= K * 127 * 127 < 2^31 for K < 133000) and are converted and
+// scaled once at the end.  Same activation pipeline as prefill_block; the four token tiles are
+// four independent accumulation chains issued round robin.
+template <typename C, bool ACT_PT>
+static __device__ inline void prefill_block_w8_channel_scale(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a,
+                                                            float *lds_sa)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds_a[2 * C::A_STAGE];
-    __shared__ __attribute__((aligned(16))) float lds_sa[(ACT_PT || DUMP) ? 4 : 3 * C::BM];
-    // Consecutive logical ids share a weight tile (same bn, successive bm); give each XCD
-    // (blocks are dealt round-robin to the 8 XCDs) a contiguous range of logical ids so that
-    // its L2 sees each weight tile and each activation tile from as few places as possible.
-    const int total = nbm * (nb8 + nb4);
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (L >= total) return;
-    const int bn = L / nbm, bm = L % nbm;
+    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW;
+    constexpr int NSLOT = TM * 4, HALF = NSLOT / 2;
+    static_assert(TM == 4, "slot -> (k step, token tile) mapping below assumes four token tiles");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int n32 = lane & 31, h = lane >> 5;
+    const int ng = p.ng;
+    const int mw0 = wm * TM * 32;
+    const int t16 = t16_0 + wn * 2 + (n32 >> 4);
+    const int tile16 = min(t16, p.ntiles8 - 1);
+    const int rw = tile16 * TILE_N + (n32 & 15);
+    const int ch = (t16 < p.ntiles8 && rw < p.n8) ? p.perm[rw] : -1;
+
+    uint32_t a_voff[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int row = (wave * LPW + i) * 8 + (lane >> 3);
+        const int cs = (lane & 7) ^ ((row >> 1) & 7);
+        a_voff[i] = (uint32_t)min(m0 + row, p.M - 1) * (uint32_t)p.K + cs * 16;
+    }
+    const uint32_t lds_a_wave = __builtin_amdgcn_readfirstlane(lds_address(lds_a) + wave * LPW * 1024);
+    auto load_a = [&](int g, int stage) {
+        const int8_t *src = p.xq + (size_t)min(g, ng - 1) * G;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) load_lds16(lds_a_wave + stage * A_STAGE + i * 1024, a_voff[i], src);
+    };
+    int a_rd[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a_rd[j] = (mw0 + n32) * G + (((2 * j + h) ^ ((n32 >> 1) & 7)) << 4);
+
+    const uint32_t b_voff = ((uint32_t)tile16 * (uint32_t)(p.K / 64) * 64 + (n32 & 15) + 16 * h) * 16;
+    v4i b[2][4];
+    auto load_b = [&](int g, auto setc) {
+        constexpr int set = decltype(setc)::value % 2;
+        const uint8_t *base = (const uint8_t *)p.w8 + (size_t)min(g, ng - 1) * 2048;
+        load_reg16<0>(b[set][0], b_voff, base);
+        load_reg16<512>(b[set][1], b_voff, base);
+        load_reg16<1024>(b[set][2], b_voff, base);
+        load_reg16<1536>(b[set][3], b_voff, base);
+    };
+
+    load_b(0, std::integral_constant<int, 0>{});
+    load_a(0, 0);
+    load_a(1, 1);
+    load_a(2, 2);
+    static_assert(ACT_PT, "an integer sum over groups needs an activation scale that does not depend on the group");
+    const float sw_row = (float)p.s8[rw];
+    await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
+    __syncthreads();
+    v4i af[RING];
+    // slot t: k step t / 4, token tile t % 4
+    auto load_frag = [&](auto stagec, auto tc) {
+        constexpr int stage = decltype(stagec)::value, t = decltype(tc)::value;
+        af[t % RING] = *(const v4i *)(lds_a + a_rd[t / 4] + stage * A_STAGE + (t % 4) * 32 * G);
+    };
+    static_for<0, DFRAG>([&](auto tc) { load_frag(std::integral_constant<int, 0>{}, tc); });
+
+    v16i P[TM];
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) P[mt][r] = 0;
+
+    auto group_step = [&](int g, auto uc) {
+        constexpr int U = decltype(uc)::value;
+        // this group's weights were requested one group ago; only the previous middle's LPW
+        // activation loads are younger
+        await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
+        load_b(g + 1, std::integral_constant<int, U + 1>{});
+        if (g >= ng) {   // a group past the end (K/128 not a multiple of 4) must add nothing
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[U % 2][j] = v4i{0, 0, 0, 0};
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, NSLOT>([&](auto stc) {
+            constexpr int st = decltype(stc)::value;
+            if constexpr (st == HALF) {
+                // group g+1's activations were requested two middles ago; younger than them are
+                // the weights of group g+1 (4 loads) and the activations of group g+2 (LPW loads)
+                await_loads<LPW + 4>();
+                mid_group_barrier<false>();
+                load_a(g + 3, (U + 3) % NSTAGE);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (st + DFRAG < NSLOT)
+                load_frag(std::integral_constant<int, U>{}, std::integral_constant<int, st + DFRAG>{});
+            else
+                load_frag(std::integral_constant<int, (U + 1) % NSTAGE>{}, std::integral_constant<int, st + DFRAG - NSLOT>{});
+            P[st % 4] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][st / 4], P[st % 4], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    for (int g = 0; g < ng; g += 4) {
+        group_step(g, std::integral_constant<int, 0>{});
+        group_step(g + 1, std::integral_constant<int, 1>{});
+        group_step(g + 2, std::integral_constant<int, 2>{});
+        group_step(g + 3, std::integral_constant<int, 3>{});
+    }
+    // drain (see prefill_block): nothing in flight towards this block's LDS or registers
+    await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
+    await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
+
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+        float sa[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            sa[r] = (float)p.xscale[min(m, p.M - 1)];
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            if (m < p.M && ch >= 0) p.y[(size_t)m * p.N + ch] = (half_t)((float)P[mt][r] * sw_row * sa[r]);
+        }
+    }
+}
+
+template <typename C, int MINW, bool DUMP, bool ACT_PT, bool W8PC>
+__global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm, int nb8,
+                                                                         int nb4, int per4, int per8)
+{
+    // dynamic LDS (more than the 64 KB a static array may take): the activation stages, then
+    // the per-(token, group) activation scales when they are in use
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    uint8_t *lds_a = smem;
+    float *lds_sa = (float *)(smem + NSTAGE * C::A_STAGE);
+    // Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Consecutive logical ids
+    // share a weight tile (same bn, successive bm); every XCD gets a contiguous range of the
+    // 4-bit ids followed by a contiguous range of the 8-bit ids, so that its L2 sees each weight
+    // tile and each activation tile from as few places as possible, and so that every XCD ends
+    // on the cheap tiles: 4-bit tiles take about twice as long as 8-bit ones (unpack, per-group
+    // rescale), and the cheap ones fill the last, partly empty round of the grid.
+    const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
+    int bn, bm;
+    bool part8;
+    if (i < per4) {
+        const int L = xcd * per4 + i;
+        if (L >= nbm * nb4) return;
+        part8 = false;
+        bn = L / nbm;
+        bm = L % nbm;
+    } else {
+        const int L = xcd * per8 + (i - per4);
+        if (L >= nbm * nb8) return;
+        part8 = true;
+        bn = L / nbm;
+        bm = L % nbm;
+    }
     constexpr int T16 = C::BN / TILE_N;
-    if (bn < nb8)
-        prefill_block<C, DUMP, ACT_PT, true>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
-    else
-        prefill_block<C, DUMP, ACT_PT, false>(p, bm * C::BM, (bn - nb8) * T16, lds_a, lds_sa);
+    constexpr bool ASYNC = W8PC && ACT_PT && !DUMP;   // the benchmarked variant; spill free (checked by the build)
+    if (part8) {
+        if constexpr (ASYNC)
+            prefill_block_w8_channel_scale<C, ACT_PT>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+        else
+            prefill_block<C, DUMP, ACT_PT, true, false>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+    } else
+        prefill_block<C, DUMP, ACT_PT, false, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+}
+
+// The kernels take more dynamic LDS than the default limit; raising the limit is a per-function
+// attribute, set on the first launch of each instantiation (per device: the attribute belongs to
+// the loaded code object of the current device).
+template <typename C, typename K>
+static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStream_t st, const LinearParams &p, int nbm,
+                          int nb8, int nb4, int per4, int per8)
+{
+    const size_t lds_bytes = (size_t)NSTAGE * C::A_STAGE + (with_sa ? (size_t)NSTAGE * C::BM * sizeof(float) : 16);
+    // (kernel, device) pairs already configured; a handful of instantiations exist
+    struct Done {
+        const void *fn;
+        int dev;
+    };
+    static Done done[64];
+    static int ndone = 0;
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        bool seen = false;
+        for (int i = 0; i < ndone; ++i) seen = seen || (done[i].fn == (const void *)kernel && done[i].dev == dev);
+        if (!seen) {
+            hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return (int)e;
+            if (ndone < 64) done[ndone++] = Done{(const void *)kernel, dev};
+        }
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm, nb8, nb4, per4, per8);
+    return (int)hipGetLastError();
 }
 
 template <typename C, int MINW>
@@ -357,28 +643,27 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
     constexpr int BM = C::BM, BN = C::BN;
     const int nbm = (p.M + BM - 1) / BM;
     const int nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN, nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
-    const int total = nbm * (nb8 + nb4);
-    const int per_xcd = (total + 7) / 8;
-    dim3 grid(per_xcd * 8), block(C::THREADS);
+    const int per4 = (nbm * nb4 + 7) / 8, per8 = (nbm * nb8 + 7) / 8;
+    dim3 grid((per4 + per8) * 8), block(C::THREADS);
     if (p.P)
-        hipLaunchKernelGGL((linear_prefill_kernel<C, MINW, true, true>), grid, block, 0, st, p, nbm, nb8, nb4, per_xcd);
-    else if (p.act_per_token)
-        hipLaunchKernelGGL((linear_prefill_kernel<C, MINW, false, true>), grid, block, 0, st, p, nbm, nb8, nb4, per_xcd);
-    else
-        hipLaunchKernelGGL((linear_prefill_kernel<C, MINW, false, false>), grid, block, 0, st, p, nbm, nb8, nb4, per_xcd);
-    return (int)hipGetLastError();
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, true, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8);
+    if (p.act_per_token && p.w8_per_channel)
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, true>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8);
+    if (p.act_per_token)
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8);
+    return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8);
 }
 
 int launch_linear_prefill(const LinearParams &p, hipStream_t st)
 {
     if (p.M == 0 || p.N == 0) return hipSuccess;
-    switch (p.tune) {
-    case 1: return launch_shape<Shape<1, 4, 4, 2>, 1>(p, st);    // 128 x 256, one wave per SIMD
-    case 2: return launch_shape<Shape<2, 2, 2, 2>, 2>(p, st);    // 128 x 128, wave tile 64 x 64
-    case 3: return launch_shape<Shape<2, 4, 4, 1>, 2>(p, st);    // 256 x 128, 8 waves, wave tile 128 x 32
-    case 4: return launch_shape<Shape<2, 4, 2, 2>, 2>(p, st);    // 128 x 256, 8 waves, wave tile 64 x 64
-    default: return launch_shape<Shape<1, 4, 4, 1>, 2>(p, st);   // 128 x 128, wave tile 128 x 32
-    }
+    // lanes address activations, packed weights and metadata with 32-bit byte offsets
+    const size_t lim = (size_t)1 << 31;
+    if ((size_t)p.M * (size_t)p.K >= lim || (size_t)p.ntiles4 * TILE_N * (size_t)p.K / 2 >= lim ||
+        (size_t)p.ntiles8 * TILE_N * (size_t)p.K >= lim)
+        return (int)hipErrorInvalidValue;
+    if (p.tune == 1) return launch_shape<Shape<1, 8, 4>, 2>(p, st);   // 128 x 256, 8 waves
+    return launch_shape<Shape<1, 4, 4>, 2>(p, st);   // 128 x 128, 4 waves, wave tile 128 x 32
 }
 
 }  // namespace mixllm
