@@ -20,9 +20,21 @@
 //    does not depend on the group.
 //  * Epilogue scatters fp16 results to their original channel (Sec. 3.4).
 // 8-bit tiles and 4-bit tiles are different block ranges of the same launch.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace mixllm {
+
+// compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
+template <int I, int N, typename F>
+static __device__ inline void static_for_dec(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for_dec<I + 1, N>(f);
+    }
+}
 
 template <int TPW, bool PART8>
 struct WChunk {   // weights and group metadata of 4 consecutive groups
@@ -259,6 +271,272 @@ static int launch_wpb(const LinearParams &p, int wpb, hipStream_t st)
     }
 }
 
+// ---- resident-activation variant -------------------------------------------------------------
+// The streaming variant above re-reads the activation fragments for every tile: at M = 16 that
+// is twice the L1 traffic of the weights themselves, and at any M most of its vector-memory
+// instructions.  Here a block of WPB waves walks a contiguous range of tiles, slab by slab: a
+// slab is WPB * 4 quantization groups of K, wave w owns groups 4w..4w+3 of it, and keeps the A
+// fragments of those groups in registers for all tiles of the block.  Per (slab, tile) item a
+// wave issues only the weight, metadata and channel-index loads, D - 1 items ahead of the one
+// it computes (a ring of D register sets), and the K-split partial outputs meet in LDS once
+// per item (double buffered: one barrier per item).  With several slabs the finishing wave of
+// a tile carries the tile's running sum in LDS.
+//
+// Integer pipeline of a 4-bit group, with the zero point hoisted out of the unpack:
+//   sum_k a (q - z) = sum_k a q  -  z * sum_k a
+// The nibbles go to the MFMA as they are (two mask/shift instructions per 8 weights instead of
+// seven), and sum_k a per (token, group) comes from one more MFMA pair per group against an
+// all-ones operand, computed once per slab because the activations are resident.  Everything
+// is int32 and exact, so the group partial sums are bit-identical to the plain definition.
+// NR = number of accumulator registers that matter (1 when M = 1: token 0 is register 0).
+// The barrier is written out: __syncthreads() would also wait for the prefetched loads.
+constexpr int RES_MAX_TILES = 16;   // tiles per block the LDS running sums provide for
+
+static __device__ inline void tile_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <bool PART8>
+struct ResItem {   // one (slab, tile) item of one wave: 4 groups of one tile
+    v4i w[4][PART8 ? 2 : 1];
+    uint2 s;        // 4 fp16 group scales
+    uint32_t z;     // 4 uint4 zero points in the low 16 bits
+    int ch;         // original channel of this lane's column, -1 for a padding row
+    half_t sw_row;  // per-channel scale of an 8-bit row
+};
+
+template <int WPB, int D, int NR, bool DUMP, bool ACT_PT, bool PART8>
+static __device__ inline void decode_resident(const LinearParams &p, int tile_begin, int tile_end,
+                                              float (*red)[WPB][NR][64], float (*tacc)[NR][64])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, ks = lane >> 4;
+    const int nrows = PART8 ? p.n8 : p.n4;
+    const int joff = PART8 ? 0 : p.n8;
+    const int nsteps = p.K / 64;
+    const int ng = p.ng;
+    const int nquads = (ng + 3) / 4;
+    const int nslab = (nquads + WPB - 1) / WPB;
+    const int ntl = tile_end - tile_begin;
+    const int total = nslab * ntl;   // items, slab-major: f -> slab f / ntl, tile tile_begin + f % ntl
+    const bool per_group_s8 = PART8 && !p.w8_per_channel;
+
+    const int8_t *xrow = p.xq + (size_t)min(c, p.M - 1) * p.K + ks * 16;
+    float xs[NR];   // per-token activation scales of rows 4ks..
+#pragma unroll
+    for (int r = 0; r < NR; ++r) xs[r] = (ACT_PT && !DUMP) ? (float)p.xscale[min(4 * ks + r, p.M - 1)] : 1.0f;
+
+    // resident state of the current slab
+    v4i a[4][2];
+    int S[4][NR];        // sum_k a per (group, row) (4-bit tiles only)
+    float sa[4][NR];     // per-(token, group) activation scales (unused when per token)
+    auto load_slab = [&](int slab) {
+        const int g0 = 4 * min(slab * WPB + wave, nquads - 1);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int gc = min(g0 + u, ng - 1);
+            a[u][0] = *(const v4i *)(xrow + (size_t)gc * G);
+            a[u][1] = *(const v4i *)(xrow + (size_t)gc * G + 64);
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                sa[u][r] = (!ACT_PT && !DUMP) ? (float)p.xscale[(size_t)min(4 * ks + r, p.M - 1) * ng + gc] : 1.0f;
+        }
+        if (!PART8) {
+            const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v4i t = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][0], ones, v4i{0, 0, 0, 0}, 0, 0, 0);
+                t = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][1], ones, t, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < NR; ++r) S[u][r] = t[r];
+            }
+        }
+    };
+
+    // byte offsets that do not change from item to item
+    constexpr int GB = PART8 ? 2048 : 1024;                       // bytes of one group of one tile
+    const size_t tile_bytes = (size_t)ng * GB;
+    const uint8_t *wlane = (PART8 ? (const uint8_t *)p.w8 : p.w4) + (size_t)tile_begin * tile_bytes + lane * 16;
+    auto load = [&](int slab, int tl, ResItem<PART8> &t) {
+        const int row = (tile_begin + tl) * TILE_N + c;
+        const int g0 = 4 * min(slab * WPB + wave, nquads - 1);
+        const uint8_t *wb = wlane + (size_t)tl * tile_bytes + (size_t)g0 * GB;
+        const int last = ng - 1 - g0;   // at the ragged end of K the last group is re-read (its scale is forced to zero)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int du = min(u, last);
+            t.w[u][0] = __builtin_nontemporal_load((const v4i *)(wb + du * GB));
+            if (PART8) t.w[u][PART8 ? 1 : 0] = __builtin_nontemporal_load((const v4i *)(wb + du * GB + 1024));
+        }
+        t.s = make_uint2(0, 0);
+        t.z = 0;
+        t.sw_row = (half_t)0.0f;
+        if (!PART8) {
+            if (!DUMP) t.s = *(const uint2 *)(p.s4 + (size_t)row * p.ngp + g0);
+            t.z = *(const uint16_t *)(p.z4 + (size_t)row * (p.ngp / 2) + g0 / 2);
+        } else if (!DUMP) {
+            if (per_group_s8) t.s = *(const uint2 *)(p.s8 + (size_t)row * p.ngp + g0);
+            else t.sw_row = p.s8[row];
+        }
+        const int ch = p.perm[min(joff + row, p.N - 1)];
+        t.ch = row < nrows ? ch : -1;
+    };
+
+    float acc[NR];
+    auto compute = [&](int slab, const ResItem<PART8> &t) {
+        const int q = slab * WPB + wave;
+        half_t sh[4];
+        __builtin_memcpy(sh, &t.s, 8);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) acc[r] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int g = 4 * q + u;
+            const bool gvalid = q < nquads && g < ng;
+            v4i P;
+            float sw;
+            if (PART8) {
+                P = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][0], t.w[u][0], v4i{0, 0, 0, 0}, 0, 0, 0);
+                P = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][1], t.w[u][PART8 ? 1 : 0], P, 0, 0, 0);
+                sw = per_group_s8 ? (float)sh[u] : (float)t.sw_row;
+            } else {
+                const v4i w = t.w[u][0];
+                const int m4 = 0x0F0F0F0F;
+                const v4i b0 = {w[0] & m4, (int)((uint32_t)w[0] >> 4) & m4, w[1] & m4, (int)((uint32_t)w[1] >> 4) & m4};
+                const v4i b1 = {w[2] & m4, (int)((uint32_t)w[2] >> 4) & m4, w[3] & m4, (int)((uint32_t)w[3] >> 4) & m4};
+                P = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][0], b0, v4i{0, 0, 0, 0}, 0, 0, 0);
+                P = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][1], b1, P, 0, 0, 0);
+                const int z = (int)((t.z >> (4 * u)) & 15);
+#pragma unroll
+                for (int r = 0; r < NR; ++r) P[r] -= z * S[u][r];
+                sw = (float)sh[u];
+            }
+            if (!gvalid) sw = 0.0f;   // a clamped re-read past the end of K contributes nothing
+            if (DUMP) {
+                if (gvalid && t.ch >= 0) {
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        const int m = 4 * ks + r;
+                        if (m < p.M) p.P[((size_t)m * p.N + t.ch) * ng + g] = P[r];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) acc[r] = __builtin_fmaf((float)P[r], ACT_PT ? sw : sw * sa[u][r], acc[r]);
+            }
+        }
+    };
+    // partial outputs of the item to LDS, one barrier, one wave sums them up
+    auto finish = [&](int slab, int tl, int par, const ResItem<PART8> &t) {
+        if (DUMP) return;
+        if (WPB > 1) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) red[par][wave][r][lane] = acc[r];
+            tile_barrier();
+        }
+        if (WPB == 1 || wave == tl % WPB) {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                float v = acc[r];
+                if (WPB > 1) {
+                    v = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < WPB; ++w) v += red[par][w][r][lane];
+                }
+                if (slab > 0) v += tacc[tl][r][lane];
+                if (slab + 1 < nslab) {
+                    tacc[tl][r][lane] = v;   // the same wave finishes this tile in every slab
+                } else {
+                    const int m = 4 * ks + r;
+                    if (m < p.M && t.ch >= 0) p.y[(size_t)m * p.N + t.ch] = (half_t)(v * xs[r]);   // scatter, Sec. 3.4
+                }
+            }
+        }
+    };
+
+    static_assert(D % 2 == 0, "the LDS double buffer alternates with the ring position");
+    ResItem<PART8> ring[D];
+    int lslab = 0, ltl = 0;   // position of the next item to request
+    auto request = [&](ResItem<PART8> &t) {
+        load(lslab, ltl, t);
+        if (++ltl == ntl) {
+            ltl = 0;
+            ++lslab;
+        }
+    };
+    static_for_dec<0, D - 1>([&](auto dc) {
+        constexpr int d = decltype(dc)::value;
+        if (d < total) request(ring[d]);
+    });
+    int slab = 0, tl = 0;     // position of the item being computed
+    for (int f0 = 0; f0 < total; f0 += D) {
+        static_for_dec<0, D>([&](auto dc) {
+            constexpr int d = decltype(dc)::value;
+            const int f = f0 + d;
+            if (f < total) {
+                if (f + D - 1 < total) request(ring[(d + D - 1) % D]);
+                if (tl == 0) load_slab(slab);
+                compute(slab, ring[d]);
+                finish(slab, tl, d & 1, ring[d]);
+                if (++tl == ntl) {
+                    tl = 0;
+                    ++slab;
+                }
+            }
+        });
+    }
+}
+
+template <int WPB, int NR, bool DUMP, bool ACT_PT>
+__global__ __launch_bounds__(WPB * 64) void linear_decode_resident_kernel(LinearParams p, int nblk8, int per8, int per4)
+{
+    __shared__ float red[(DUMP || WPB == 1) ? 1 : 2][WPB][NR][64];
+    __shared__ float tacc[DUMP ? 1 : RES_MAX_TILES][NR][64];
+    const int b = blockIdx.x;
+    if (b < nblk8) {
+        const int t0 = b * per8;
+        decode_resident<WPB, 2, NR, DUMP, ACT_PT, true>(p, t0, min(t0 + per8, p.ntiles8), red, tacc);
+    } else {
+        const int t0 = (b - nblk8) * per4;
+        decode_resident<WPB, 4, NR, DUMP, ACT_PT, false>(p, t0, min(t0 + per4, p.ntiles4), red, tacc);
+    }
+}
+
+template <int WPB, int NR>
+static int launch_resident(const LinearParams &p, int nblk8, int per8, int nblk4, int per4, hipStream_t st)
+{
+    dim3 grid(nblk8 + nblk4), block(WPB * 64);
+    if (p.P)
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, true, true>), grid, block, 0, st, p, nblk8, per8, per4);
+    else if (p.act_per_token)
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, true>), grid, block, 0, st, p, nblk8, per8, per4);
+    else
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, false>), grid, block, 0, st, p, nblk8, per8, per4);
+    return (int)hipGetLastError();
+}
+
+// Resident variant: blocks walk contiguous tile ranges.  8-bit tiles hold twice the bytes of
+// 4-bit tiles, so an 8-bit block gets half as many tiles as a 4-bit block, and the tile counts
+// per block are the smallest for which all blocks are resident at once.
+// Returns -1 when the shape is not covered (then the streaming variant runs).
+template <int WPB>
+static int try_launch_resident(const LinearParams &p, int blocks_per_cu, hipStream_t st)
+{
+    const int slots = 256 * blocks_per_cu;   // blocks resident at once
+    auto blocks = [&](int i4) {
+        const int i8 = i4 >= 2 ? i4 / 2 : 1;
+        return (p.ntiles4 + i4 - 1) / i4 + (p.ntiles8 + i8 - 1) / i8;
+    };
+    int per4 = 1;
+    while (blocks(per4) > slots && per4 < RES_MAX_TILES) ++per4;
+    if (blocks(per4) > slots) return -1;
+    const int per8 = per4 >= 2 ? per4 / 2 : 1;
+    const int nblk8 = (p.ntiles8 + per8 - 1) / per8, nblk4 = (p.ntiles4 + per4 - 1) / per4;
+    return p.M == 1 ? launch_resident<WPB, 1>(p, nblk8, per8, nblk4, per4, st)
+                    : launch_resident<WPB, 4>(p, nblk8, per8, nblk4, per4, st);
+}
+
 // Launch shape (from sweeps on the Llama-shaped layers): at most 8 waves per CU in total; K
 // is split WPB ways inside a block when there are too few tiles for that, and a wave takes
 // two tiles when M is large enough for the activation traffic to matter.
@@ -266,11 +544,19 @@ int launch_linear_decode(const LinearParams &p, hipStream_t st)
 {
     if (p.M == 0 || p.N == 0) return hipSuccess;
     const int tiles = p.ntiles8 + p.ntiles4;
+    // Resident variant where it measured faster on the Llama-shaped layers: K of one slab
+    // (K <= 4096) and either few tiles or few tokens.  tune 1..999 forces the streaming variant,
+    // tune >= 1000 the resident one (experiments).
+    const bool resident = p.tune == 0 ? (p.ng <= 32 && (tiles <= 1024 || p.M <= 4)) : p.tune >= 1000;
+    if (resident) {
+        const int rc = try_launch_resident<8>(p, 1, st);
+        if (rc >= 0) return rc;
+    }
     const int nquads = (p.ng + 3) / 4;
     int tpw = (tiles >= 300 && p.M > 4) ? 2 : 1;
     int wpb = 1;
     while (wpb < 8 && wpb * 2 <= nquads && tiles * wpb * 2 <= 2048) wpb *= 2;
-    if (p.tune > 0) {   // experiments: tune = 100 * tpw + wpb
+    if (p.tune > 0 && p.tune < 900) {   // experiments: tune = 100 * tpw + wpb
         tpw = p.tune / 100;
         wpb = p.tune % 100;
     }

@@ -34,7 +34,45 @@ static __device__ inline uint2 quant8(const h8 &v, float s)
     return make_uint2(w[0], w[1]);
 }
 
-// One block per token; the row is read twice (the second read hits L2).
+// One block per token, the row held in registers between the absmax pass and the quantizing
+// pass (up to NV vectors of 8 per thread: K <= 2048 * NV): one trip to memory instead of two,
+// which is most of the duration of this kernel when M is small.
+template <int NV>
+__global__ __launch_bounds__(256) void act_quant_per_token_regs(const half_t *__restrict__ x,
+                                                                int8_t *__restrict__ xq,
+                                                                half_t *__restrict__ xs, int K)
+{
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    const h8 *row = (const h8 *)(x + (size_t)m * K);
+    const int nvec = K / 8;
+    h8 d[NV];
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int v = threadIdx.x + 256 * j;
+        if (v < nvec) {
+            d[j] = row[v];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)d[j][i]));
+        }
+    }
+    amax = wave_max(amax);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    half_t s16 = store_scale(amax / 127.0f);
+    float s = (float)s16;
+    if (threadIdx.x == 0) xs[m] = s16;
+    uint2 *out = (uint2 *)(xq + (size_t)m * K);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int v = threadIdx.x + 256 * j;
+        if (v < nvec) out[v] = quant8(d[j], s);
+    }
+}
+
+// One block per token, any K; the row is read twice (the second read hits L2).
 __global__ __launch_bounds__(256) void act_quant_per_token(const half_t *__restrict__ x,
                                                            int8_t *__restrict__ xq,
                                                            half_t *__restrict__ xs, int K)
@@ -85,8 +123,15 @@ int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq,
 {
     if (d.M == 0) return hipSuccess;
     if (d.act_group == d.K) {
-        hipLaunchKernelGGL(act_quant_per_token, dim3(d.M), dim3(256), 0, st, (const half_t *)x, xq,
-                           (half_t *)xs, d.K);
+        if (d.K <= 2048 * 2)
+            hipLaunchKernelGGL(act_quant_per_token_regs<2>, dim3(d.M), dim3(256), 0, st, (const half_t *)x, xq,
+                               (half_t *)xs, d.K);
+        else if (d.K <= 2048 * 8)
+            hipLaunchKernelGGL(act_quant_per_token_regs<8>, dim3(d.M), dim3(256), 0, st, (const half_t *)x, xq,
+                               (half_t *)xs, d.K);
+        else
+            hipLaunchKernelGGL(act_quant_per_token, dim3(d.M), dim3(256), 0, st, (const half_t *)x, xq,
+                               (half_t *)xs, d.K);
     } else {
         const int ng = d.K / G;
         hipLaunchKernelGGL(act_quant_per_group, dim3(d.M, (ng + 15) / 16), dim3(256), 0, st,
