@@ -86,15 +86,17 @@ def main():
         xs_ = [torch.from_numpy(synth.make_x(M, l.K, seed=7, tag="x/" + l.name)).to(dev) for l in layers]
         bufs = [(torch.empty((M, l.K), dtype=torch.int8, device=dev),
                  torch.empty((M, 1), dtype=torch.float16, device=dev),
-                 torch.empty((M, l.N), dtype=torch.float16, device=dev)) for l in layers]
+                 torch.empty((M, l.N), dtype=torch.float16, device=dev),
+                 torch.empty(mx.query_sizes(M, l.K, l.N, l.n8)["workspace_bytes"], dtype=torch.uint8, device=dev))
+                for l in layers]
         return xs_, bufs
 
     def step(i, xs_, bufs):
         ws = copies[i % n_copies]
         for li in range(len(layers)):
-            xq, xsc, y = bufs[li]
-            mx.quantize_activations(xs_[li], out=(xq, xsc))
-            mx.mixed_linear(xq, xsc, ws[li], out=y)
+            # the whole hot path from fp16 activations: one fused kernel where the library has one
+            # (M = 1, K <= 4096), otherwise activation quantizer + linear
+            mx.linear_fp16(xs_[li], ws[li], out=bufs[li][2], workspace=bufs[li][3])
 
     def time_steps(M, steps, warmup):
         """Seconds per step.  Decode steps are launch bound when driven from Python (8 ctypes
@@ -141,29 +143,51 @@ def main():
         return (time.perf_counter() - t) / steps
 
     def time_dominant(M, reps, li):
-        """Average duration of one launch of the linear kernel of layer `li`, each launch
-        bracketed by its own pair of HIP events on the launch stream."""
+        """Average duration of one launch of the linear kernel of layer `li`: `reps` launches
+        (weight copies rotating) recorded into one HIP graph, the replay bracketed by one pair
+        of HIP events on the launch stream, so that neither Python nor event handling sits
+        between two launches.  This is the figure a rocprofv3 kernel trace of the same kernel
+        has to agree with.  Also returned: the mean over launches that each have their own event
+        pair (includes ~2 us of event and launch handling per launch)."""
         xs_, bufs = make_acts(M)
-        xq, xsc, y = bufs[li]
+        xq, xsc, y, _ = bufs[li]
         mx.quantize_activations(xs_[li], out=(xq, xsc))
-        for i in range(10):
+        for i in range(max(10, reps)):      # warm: clocks settle over tens of milliseconds at large M
             mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         torch.cuda.synchronize()
+
+        def burst():
+            for i in range(reps):
+                mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+
+        replay = burst
+        if not args.no_graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    burst()
+            torch.cuda.current_stream().wait_stream(side)
+            replay = graph.replay
+        replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        nrep = 3
+        a.record()
+        for _ in range(nrep):
+            replay()
+        b.record()
+        torch.cuda.synchronize()
+        t_graph = a.elapsed_time(b) * 1e-3 / (reps * nrep)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for i, (a, b) in enumerate(evs):
             a.record()
             mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
             b.record()
         torch.cuda.synchronize()
         ts = np.array([a.elapsed_time(b) for a, b in evs]) * 1e-3
-        # and back to back between one pair of events (includes launch gaps)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for i in range(reps):
-            mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
-        b.record()
-        torch.cuda.synchronize()
-        return float(ts.mean()), float(np.median(ts)), a.elapsed_time(b) * 1e-3 / reps
+        return t_graph, float(ts.mean())
 
     def step_bytes(M):
         return sum(layer_alg_bytes(l.K, l.N, l.n8, M) + quant_alg_bytes(l.K, M) for l in layers)
@@ -175,20 +199,20 @@ def main():
 
     def leg(M, steps, warmup, reps):
         sec = time_steps(M, steps, warmup)
-        k_mean, k_med, k_b2b = time_dominant(M, reps, dom)
+        k_graph, k_pair = time_dominant(M, reps, dom)
         l = layers[dom]
         out = {"M": M, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9,
                "TOPS": step_ops(M) / sec / 1e12,
-               "dominant_kernel": {"layer": l.name, "us_event_mean": k_mean * 1e6, "us_event_median": k_med * 1e6,
-                                   "us_back_to_back": k_b2b * 1e6,
-                                   "GBps": layer_alg_bytes(l.K, l.N, l.n8, M) / k_mean / 1e9,
-                                   "TOPS": 2.0 * M * l.K * l.N / k_mean / 1e12}}
+               "dominant_kernel": {"layer": l.name, "us_per_launch": k_graph * 1e6,
+                                   "us_with_own_event_pair": k_pair * 1e6,
+                                   "GBps": layer_alg_bytes(l.K, l.N, l.n8, M) / k_graph / 1e9,
+                                   "TOPS": 2.0 * M * l.K * l.N / k_graph / 1e12}}
         log(f"[bench] M={M}: {out['ms_per_step']:.4f} ms/step, {out['GBps']:.0f} GB/s, {out['TOPS']:.1f} TOPS; "
-            f"{l.name} kernel {k_mean * 1e6:.1f} us (median {k_med * 1e6:.1f}, b2b {k_b2b * 1e6:.1f})")
+            f"{l.name} kernel {k_graph * 1e6:.1f} us per launch ({k_pair * 1e6:.1f} with its own event pair)")
         return out
 
-    primary = leg(M0, args.steps, args.warmup, min(args.steps, 200))
     decode_like = M0 <= 16
+    primary = leg(M0, args.steps, args.warmup if decode_like else max(args.warmup, 40), min(args.steps, 200) if decode_like else 30)
     l = layers[dom]
     if decode_like:
         roof = {"bound": "hbm", "achieved": primary["dominant_kernel"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
@@ -204,7 +228,7 @@ def main():
         roof["traffic"] = json.load(open(tpath)).get(key)
     roof["algorithmic"] = layer_alg_bytes(l.K, l.N, l.n8, M0) if decode_like else 2.0 * M0 * l.K * l.N
     roof["kernel"] = f"mixed_linear {'decode' if decode_like else 'prefill'} path, layer {l.name} K={l.K} N={l.N} M={M0}"
-    roof["us_per_launch"] = primary["dominant_kernel"]["us_event_mean"]
+    roof["us_per_launch"] = primary["dominant_kernel"]["us_per_launch"]
 
     result = {
         "metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)",
@@ -241,9 +265,9 @@ def main():
     if not args.no_extras:
         sweep = []
         for M in ([4, 8, 16] if decode_like else [512]):
-            sweep.append(leg(M, max(20, args.steps // 4), 5, 50))
+            sweep.append(leg(M, max(20, args.steps // 4), 5 if decode_like else 40, 50 if decode_like else 30))
         result["sweep"] = sweep
-        other = leg(2048 if decode_like else 1, 20 if decode_like else 100, 3, 30)
+        other = leg(2048 if decode_like else 1, 40 if decode_like else 100, 40 if decode_like else 3, 30)
         key = "prefill" if decode_like else "decode"
         if decode_like:
             other["roofline"] = {"bound": "mfma", "achieved": other["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS,

@@ -85,7 +85,8 @@ typedef struct mixllm_desc {
 typedef struct mixllm_sizes {
     size_t w8_bytes, w4_bytes, scales8_bytes, scales4_bytes, zeros4_bytes, perm_bytes;
     size_t xq_bytes, xscale_bytes, y_bytes;
-    size_t workspace_bytes;   /* scratch for mixllm_mixed_linear; currently always 0 */
+    size_t workspace_bytes;   /* scratch for mixllm_mixed_linear_fp16 (xq, then xscale, each rounded up to
+                                 256 B); mixllm_mixed_linear itself needs none */
 } mixllm_sizes;
 
 const char *mixllm_status_string(int status);
@@ -154,8 +155,8 @@ int mixllm_quantize_activations(const mixllm_desc *d, const void *x, int8_t *xq,
  * The quantized linear (Fig. 1; Sec. 3.3 two-step dequantization; Sec. 3.4 scatter):
  *   P[m,j,g]  = sum_{k in group g} xq[m,k] * (q4[j,k] - z[j,g])   (int32, exact; 8-bit rows: q8)
  *   y[m, feature_perm[j]] = fp16( sum_g float(P[m,j,g]) * s_w[j,g] * s_a[m,g] )   (fp32 sums)
- * One launch covers both parts.  M = 0 is a no-op.  workspace may be NULL when
- * workspace_bytes (from mixllm_query_sizes) is 0.
+ * One launch covers both parts.  M = 0 is a no-op.  workspace is not used by this call
+ * (NULL and 0 are fine); the parameters are kept for callers that size one buffer for all calls.
  * Errors: EINVAL, EUNSUPPORTED (path cannot run this shape, e.g. DECODE with M > 16),
  * EWORKSPACE, EHIP.
  */
@@ -164,7 +165,23 @@ int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xsca
                         const void *scales8, const void *zeros4, const int32_t *feature_perm,
                         void *y, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Same, with the kernel chosen by the caller (MIXLLM_PATH_*); for tests and benchmarks. */
+/*
+ * Activation quantizer and quantized linear in one call (Fig. 1 end to end: fp16 activations in,
+ * fp16 outputs in the original channel order out):
+ *   x fp16 [M][K] -> y fp16 [M][N], same definition as mixllm_quantize_activations followed by
+ *   mixllm_mixed_linear, with bit-identical results.
+ * For M = 1 and K <= 4096 this is ONE kernel: every block of the decode kernel quantizes the
+ * activations itself while its first weight loads are in flight, and `workspace` is not
+ * touched (may be NULL).  Otherwise the two kernels run back to back on `stream` with xq and
+ * xscale placed in `workspace` (at least mixllm_query_sizes().workspace_bytes, 16-byte aligned).
+ * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP.  M = 0 is a no-op.
+ */
+int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *packed_w4,
+                             const void *packed_w8, const void *scales4, const void *scales8,
+                             const void *zeros4, const int32_t *feature_perm, void *y, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* Same as mixllm_mixed_linear, with the kernel chosen by the caller (MIXLLM_PATH_*); for tests and benchmarks. */
 int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void *xscale,
                              const void *packed_w4, const void *packed_w8, const void *scales4,
                              const void *scales8, const void *zeros4, const int32_t *feature_perm,

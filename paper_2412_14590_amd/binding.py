@@ -56,9 +56,11 @@ def lib():
         L.mixllm_mixed_linear.argtypes = [C.POINTER(_Desc)] + [_VP] * 10 + [C.c_size_t, _VP]
         L.mixllm_mixed_linear_path.argtypes = [C.POINTER(_Desc)] + [_VP] * 10 + [C.c_size_t, C.c_int, _VP]
         L.mixllm_debug_group_partials.argtypes = [C.POINTER(_Desc)] + [_VP] * 6 + [C.c_int, _VP]
+        L.mixllm_mixed_linear_fp16.argtypes = [C.POINTER(_Desc)] + [_VP] * 9 + [C.c_size_t, _VP]
         for name in ("mixllm_query_sizes", "mixllm_build_feature_perm", "mixllm_quantize_weights",
                      "mixllm_pack_weights", "mixllm_unpack_weights", "mixllm_quantize_activations",
-                     "mixllm_mixed_linear", "mixllm_mixed_linear_path", "mixllm_debug_group_partials"):
+                     "mixllm_mixed_linear", "mixllm_mixed_linear_path", "mixllm_debug_group_partials",
+                     "mixllm_mixed_linear_fp16"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -228,3 +230,23 @@ def linear(x: torch.Tensor, L: PackedLayer, act_group=None, path: int = PATH_AUT
     """fp16 x [M,K] -> fp16 y [M,N]: activation quantizer followed by the quantized linear."""
     xq, xs = quantize_activations(x, act_group)
     return mixed_linear(xq, xs, L, path)
+
+
+def linear_fp16(x: torch.Tensor, L: PackedLayer, act_group=None, out=None, workspace=None) -> torch.Tensor:
+    """fp16 x [M,K] -> fp16 y [M,N] through mixllm_mixed_linear_fp16: one kernel for M = 1 and
+    K <= 4096 (the decode kernel quantizes its own activations), otherwise quantizer + linear with
+    xq / xscale in `workspace` (a uint8 tensor of query_sizes()['workspace_bytes'], allocated here
+    when not given)."""
+    assert x.dtype == torch.float16 and x.dim() == 2
+    M, K = x.shape
+    assert K == L.K
+    d = L.desc(M, act_group)
+    y = torch.empty((M, L.N), dtype=torch.float16, device=x.device) if out is None else out
+    need = query_sizes(M, K, L.N, L.n8, act_group, L.w8_group)["workspace_bytes"]
+    if workspace is None and not (M == 1 and K <= 4096):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    wb = 0 if workspace is None else workspace.numel()
+    _check(lib().mixllm_mixed_linear_fp16(C.byref(d), _ptr(x), _ptr(L.w4), _ptr(L.w8), _ptr(L.s4), _ptr(L.s8),
+                                          _ptr(L.z4), _ptr(L.perm), _ptr(y), _ptr(workspace), wb, _stream()),
+           "mixllm_mixed_linear_fp16")
+    return y

@@ -9,6 +9,8 @@ using namespace mixllm;
 
 namespace {
 
+inline size_t round_up_sz(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 // A buffer argument: must be non-null and 16-byte aligned when its size is non-zero.
@@ -39,7 +41,8 @@ void sizes_of(const mixllm_desc &d, mixllm_sizes &s)
     s.xq_bytes = (size_t)d.M * (size_t)d.K;
     s.xscale_bytes = (size_t)d.M * (size_t)(d.K / d.act_group) * 2;
     s.y_bytes = (size_t)d.M * (size_t)d.N * 2;
-    s.workspace_bytes = 0;
+    // scratch of mixllm_mixed_linear_fp16 when it cannot quantize inside the linear kernel: xq, then xscale
+    s.workspace_bytes = (size_t)round_up_sz(s.xq_bytes, 256) + (size_t)round_up_sz(s.xscale_bytes, 256);
 }
 
 LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xscale, const void *w4,
@@ -244,6 +247,41 @@ int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xsca
 {
     return mixllm_mixed_linear_path(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4,
                                     feature_perm, y, workspace, workspace_bytes, MIXLLM_PATH_AUTO, stream);
+}
+
+int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *packed_w4, const void *packed_w8,
+                             const void *scales4, const void *scales8, const void *zeros4,
+                             const int32_t *feature_perm, void *y, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    if (d->M == 0) return MIXLLM_OK;
+    mixllm_sizes s;
+    sizes_of(*d, s);
+    if (!x || !aligned16(x) || !y || !aligned16(y) || !feature_perm || !aligned16(feature_perm)) return MIXLLM_EINVAL;
+    if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(zeros4, s.zeros4_bytes) ||
+        !buf_ok(scales8, s.scales8_bytes) || !buf_ok(scales4, s.scales4_bytes))
+        return MIXLLM_EINVAL;
+    LinearParams p = make_params(*d, nullptr, nullptr, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm);
+    p.y = (half_t *)y;
+    // One kernel when the decode path can quantize inside the linear and it pays: measured on the
+    // Llama-shaped layers the built-in quantizer wins for a single token, ties at two and loses
+    // from three on (its work is repeated by every block).  MIXLLM_TUNE=2000 takes it whenever
+    // it is possible (tests of the M = 2..4 code).
+    if (decode_can_fuse_quantizer(p) && (d->M == 1 || p.tune == 2000)) {
+        p.tune = 0;
+        p.x = (const half_t *)x;
+        return hip_status(launch_linear_decode(p, (hipStream_t)stream));
+    }
+    // two kernels: the stand-alone quantizer into the workspace, then the linear
+    if (!workspace || !aligned16(workspace)) return MIXLLM_EINVAL;
+    if (workspace_bytes < s.workspace_bytes) return MIXLLM_EWORKSPACE;
+    int8_t *xq = (int8_t *)workspace;
+    void *xscale = (uint8_t *)workspace + round_up_sz(s.xq_bytes, 256);
+    if (int rc = hip_status(launch_quantize_activations(*d, x, xq, xscale, (hipStream_t)stream))) return rc;
+    p.xq = xq;
+    p.xscale = (const half_t *)xscale;
+    return dispatch(*d, p, MIXLLM_PATH_AUTO, (hipStream_t)stream);
 }
 
 int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const void *packed_w4,

@@ -29,6 +29,7 @@ struct LinearParams {
     int act_per_token;   // 1: xscale [M], 0: xscale [M][ng]
     int w8_per_channel;  // 1: scales8 [n8p], 0: scales8 [n8p][ngp]
     int tune;            // launch-shape override for experiments (0 = library default)
+    const half_t *x;   // fp16 activations [M][K]: set only by the fused quantize + linear entry point
     const int8_t *xq;
     const half_t *xscale;
     const uint8_t *w4;
@@ -80,6 +81,24 @@ static inline __device__ v4i unpack16(uint32_t w0, uint32_t w1, uint32_t zb)
 }
 static inline __device__ uint32_t zbias(int z) { return 0x80808080u - 0x01010101u * (uint32_t)z; }
 
+// ---- activation quantizer arithmetic (Sec. 2 formula with z = 0), shared by the stand-alone
+// quantizer kernel and the decode kernel that quantizes its own activations ----
+
+// fp32 scale -> stored fp16 scale; a scale that is (or rounds to) zero becomes 1.
+static inline __device__ half_t store_scale(float s32)
+{
+    half_t s16 = (half_t)s32;   // round-to-nearest-even conversion
+    if ((float)s16 == 0.0f) s16 = (half_t)1.0f;
+    return s16;
+}
+// one int8 code: IEEE division, ties to even, clamp to [-127, 127]; returned in the low byte
+static inline __device__ uint32_t quant_code(half_t v, float s)
+{
+    float t = __builtin_rintf((float)v / s);
+    t = fminf(fmaxf(t, -127.0f), 127.0f);
+    return (uint32_t)(int)t & 0xffu;
+}
+
 // ---- launchers (defined one per .hip file); return a hipError_t as int ----
 int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq, void *xs,
                                 hipStream_t st);
@@ -93,6 +112,8 @@ int launch_unpack_weights(const mixllm_desc &d, const void *w8, const void *w4, 
                           void *s4c, uint8_t *z4c, hipStream_t st);
 int launch_linear_generic(const LinearParams &p, hipStream_t st);
 int launch_linear_decode(const LinearParams &p, hipStream_t st);
+// true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
+bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);
 
 }  // namespace mixllm

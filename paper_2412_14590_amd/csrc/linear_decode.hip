@@ -306,9 +306,26 @@ struct ResItem {   // one (slab, tile) item of one wave: 4 groups of one tile
     half_t sw_row;  // per-channel scale of an 8-bit row
 };
 
-template <int WPB, int D, int NR, bool DUMP, bool ACT_PT, bool PART8>
+// FUSED: the activations arrive as fp16 (p.x) and every block quantizes them itself while its
+// first weight loads are in flight (Sec. 2 formula, z = 0; the same arithmetic as the stand-alone
+// quantizer, so the codes are identical): wave w quantizes its own 512 k of every token row
+// (the row maxima of the waves meet in LDS), leaves the codes in LDS and picks its A fragments
+// up from there.  The work per block is that of the whole stand-alone quantizer, so this only
+// pays for very few tokens (M <= 4), and it requires a single slab (K <= WPB * 512).
+typedef half_t h8v __attribute__((ext_vector_type(8)));
+constexpr int FUSED_MAX_M = 4;
+
+template <int WPB>
+struct QuantScratch {
+    float part[WPB][FUSED_MAX_M];         // per-wave row maxima
+    float scale[WPB][FUSED_MAX_M][4];     // per wave: row scale ([0]) or the 4 group scales of its share
+    __attribute__((aligned(16))) uint8_t code[WPB][FUSED_MAX_M][512];   // int8 codes of each wave's share of K
+};
+
+template <int WPB, int D, int NR, bool DUMP, bool ACT_PT, bool PART8, bool FUSED>
 static __device__ inline void decode_resident(const LinearParams &p, int tile_begin, int tile_end,
-                                              float (*red)[WPB][NR][64], float (*tacc)[NR][64])
+                                              float (*red)[WPB][NR][64], float (*tacc)[NR][64],
+                                              QuantScratch<WPB> *qs)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, ks = lane >> 4;
@@ -322,10 +339,10 @@ static __device__ inline void decode_resident(const LinearParams &p, int tile_be
     const int total = nslab * ntl;   // items, slab-major: f -> slab f / ntl, tile tile_begin + f % ntl
     const bool per_group_s8 = PART8 && !p.w8_per_channel;
 
-    const int8_t *xrow = p.xq + (size_t)min(c, p.M - 1) * p.K + ks * 16;
+    const int8_t *xrow = FUSED ? nullptr : p.xq + (size_t)min(c, p.M - 1) * p.K + ks * 16;
     float xs[NR];   // per-token activation scales of rows 4ks..
 #pragma unroll
-    for (int r = 0; r < NR; ++r) xs[r] = (ACT_PT && !DUMP) ? (float)p.xscale[min(4 * ks + r, p.M - 1)] : 1.0f;
+    for (int r = 0; r < NR; ++r) xs[r] = (!FUSED && ACT_PT && !DUMP) ? (float)p.xscale[min(4 * ks + r, p.M - 1)] : 1.0f;
 
     // resident state of the current slab
     v4i a[4][2];
@@ -333,14 +350,68 @@ static __device__ inline void decode_resident(const LinearParams &p, int tile_be
     float sa[4][NR];     // per-(token, group) activation scales (unused when per token)
     auto load_slab = [&](int slab) {
         const int g0 = 4 * min(slab * WPB + wave, nquads - 1);
+        if (FUSED) {
+            // This wave's share of K is k in [512 wave, 512 wave + 512): lane l quantizes the 8
+            // values at 512 wave + 8 l of each token row (values past K count as zero), so every
+            // code is computed once per block, not once per lane that later uses it.
+            const int k0 = 512 * wave + 8 * lane;
+            const bool kvalid = k0 < p.K;
+            for (int r = 0; r < p.M; ++r) {
+                h8v xv;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int gc = min(g0 + u, ng - 1);
-            a[u][0] = *(const v4i *)(xrow + (size_t)gc * G);
-            a[u][1] = *(const v4i *)(xrow + (size_t)gc * G + 64);
+                for (int i = 0; i < 8; ++i) xv[i] = (half_t)0.0f;
+                if (kvalid) xv = *(const h8v *)(p.x + (size_t)r * p.K + k0);
+                float amax = 0.0f;
 #pragma unroll
-            for (int r = 0; r < NR; ++r)
-                sa[u][r] = (!ACT_PT && !DUMP) ? (float)p.xscale[(size_t)min(4 * ks + r, p.M - 1) * ng + gc] : 1.0f;
+                for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)xv[i]));
+                // 16 lanes cover one group of 128
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+                float sc;
+                if (ACT_PT) {
+                    amax = fmaxf(amax, __shfl_xor(amax, 16, 64));
+                    amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+                    if (lane == 0) qs->part[wave][r] = amax;
+                    tile_barrier();   // every wave runs this loop the same number of times
+                    float row = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < WPB; ++w) row = fmaxf(row, qs->part[w][r]);
+                    sc = (float)store_scale(row / 127.0f);
+                    if (lane == 0) qs->scale[wave][r][0] = sc;
+                } else {
+                    sc = (float)store_scale(amax / 127.0f);
+                    if ((lane & 15) == 0) qs->scale[wave][r][lane >> 4] = sc;
+                }
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w0 |= quant_code(xv[i], sc) << (8 * i);
+                    w1 |= quant_code(xv[4 + i], sc) << (8 * i);
+                }
+                *(uint2 *)&qs->code[wave][r][8 * lane] = make_uint2(w0, w1);
+            }
+            // the fragments and scales this lane needs come from other lanes of the same wave
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            const int rc = min(c, p.M - 1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a[u][0] = *(const v4i *)&qs->code[wave][rc][u * 128 + ks * 16];
+                a[u][1] = *(const v4i *)&qs->code[wave][rc][u * 128 + 64 + ks * 16];
+#pragma unroll
+                for (int r = 0; r < NR; ++r) sa[u][r] = ACT_PT ? 1.0f : qs->scale[wave][min(4 * ks + r, p.M - 1)][u];
+            }
+#pragma unroll
+            for (int r = 0; r < NR; ++r) xs[r] = ACT_PT ? qs->scale[wave][min(4 * ks + r, p.M - 1)][0] : 1.0f;
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int gc = min(g0 + u, ng - 1);
+                a[u][0] = *(const v4i *)(xrow + (size_t)gc * G);
+                a[u][1] = *(const v4i *)(xrow + (size_t)gc * G + 64);
+#pragma unroll
+                for (int r = 0; r < NR; ++r)
+                    sa[u][r] = (!ACT_PT && !DUMP) ? (float)p.xscale[(size_t)min(4 * ks + r, p.M - 1) * ng + gc] : 1.0f;
+            }
         }
         if (!PART8) {
             const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
@@ -488,18 +559,20 @@ static __device__ inline void decode_resident(const LinearParams &p, int tile_be
     }
 }
 
-template <int WPB, int NR, bool DUMP, bool ACT_PT>
+template <int WPB, int NR, bool DUMP, bool ACT_PT, bool FUSED>
 __global__ __launch_bounds__(WPB * 64) void linear_decode_resident_kernel(LinearParams p, int nblk8, int per8, int per4)
 {
     __shared__ float red[(DUMP || WPB == 1) ? 1 : 2][WPB][NR][64];
     __shared__ float tacc[DUMP ? 1 : RES_MAX_TILES][NR][64];
+    __shared__ QuantScratch<FUSED ? WPB : 1> qscratch;
+    QuantScratch<WPB> *qlds = (QuantScratch<WPB> *)&qscratch;   // only dereferenced when FUSED
     const int b = blockIdx.x;
     if (b < nblk8) {
         const int t0 = b * per8;
-        decode_resident<WPB, 2, NR, DUMP, ACT_PT, true>(p, t0, min(t0 + per8, p.ntiles8), red, tacc);
+        decode_resident<WPB, 2, NR, DUMP, ACT_PT, true, FUSED>(p, t0, min(t0 + per8, p.ntiles8), red, tacc, qlds);
     } else {
         const int t0 = (b - nblk8) * per4;
-        decode_resident<WPB, 4, NR, DUMP, ACT_PT, false>(p, t0, min(t0 + per4, p.ntiles4), red, tacc);
+        decode_resident<WPB, 4, NR, DUMP, ACT_PT, false, FUSED>(p, t0, min(t0 + per4, p.ntiles4), red, tacc, qlds);
     }
 }
 
@@ -508,11 +581,15 @@ static int launch_resident(const LinearParams &p, int nblk8, int per8, int nblk4
 {
     dim3 grid(nblk8 + nblk4), block(WPB * 64);
     if (p.P)
-        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, true, true>), grid, block, 0, st, p, nblk8, per8, per4);
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, true, true, false>), grid, block, 0, st, p, nblk8, per8, per4);
+    else if (p.x && p.act_per_token)
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, true, true>), grid, block, 0, st, p, nblk8, per8, per4);
+    else if (p.x)
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, false, true>), grid, block, 0, st, p, nblk8, per8, per4);
     else if (p.act_per_token)
-        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, true>), grid, block, 0, st, p, nblk8, per8, per4);
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, true, false>), grid, block, 0, st, p, nblk8, per8, per4);
     else
-        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, false>), grid, block, 0, st, p, nblk8, per8, per4);
+        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, false, false>), grid, block, 0, st, p, nblk8, per8, per4);
     return (int)hipGetLastError();
 }
 
@@ -540,14 +617,25 @@ static int try_launch_resident(const LinearParams &p, int blocks_per_cu, hipStre
 // Launch shape (from sweeps on the Llama-shaped layers): at most 8 waves per CU in total; K
 // is split WPB ways inside a block when there are too few tiles for that, and a wave takes
 // two tiles when M is large enough for the activation traffic to matter.
+// The resident variant takes fp16 activations when K is a single slab of 8 waves (K <= 4096).
+bool decode_can_fuse_quantizer(const LinearParams &p)
+{
+    return p.M >= 1 && p.M <= FUSED_MAX_M && p.ng <= 32 && !p.P;
+}
+
 int launch_linear_decode(const LinearParams &p, hipStream_t st)
 {
     if (p.M == 0 || p.N == 0) return hipSuccess;
+    if (p.x) {   // fused quantizer: resident variant only
+        if (!decode_can_fuse_quantizer(p)) return (int)hipErrorInvalidValue;
+        const int rc = try_launch_resident<8>(p, 1, st);
+        return rc >= 0 ? rc : (int)hipErrorInvalidValue;
+    }
     const int tiles = p.ntiles8 + p.ntiles4;
     // Resident variant where it measured faster on the Llama-shaped layers: K of one slab
-    // (K <= 4096) and either few tiles or few tokens.  tune 1..999 forces the streaming variant,
-    // tune >= 1000 the resident one (experiments).
-    const bool resident = p.tune == 0 ? (p.ng <= 32 && (tiles <= 1024 || p.M <= 4)) : p.tune >= 1000;
+    // (K <= 4096) and either few tiles or a single token.  tune 1..999 forces the streaming
+    // variant, tune >= 1000 the resident one (experiments).
+    const bool resident = p.tune == 0 ? (p.ng <= 32 && (tiles <= 1024 || p.M == 1)) : p.tune >= 1000;
     if (resident) {
         const int rc = try_launch_resident<8>(p, 1, st);
         if (rc >= 0) return rc;

@@ -565,35 +565,30 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
 
 template <typename C, int MINW, bool DUMP, bool ACT_PT, bool W8PC>
 __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm, int nb8,
-                                                                         int nb4, int per4, int per8)
+                                                                         int nb4, int per4, int per8, int band)
 {
     // dynamic LDS (more than the 64 KB a static array may take): the activation stages, then
     // the per-(token, group) activation scales when they are in use
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     uint8_t *lds_a = smem;
     float *lds_sa = (float *)(smem + NSTAGE * C::A_STAGE);
-    // Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Consecutive logical ids
-    // share a weight tile (same bn, successive bm); every XCD gets a contiguous range of the
-    // 4-bit ids followed by a contiguous range of the 8-bit ids, so that its L2 sees each weight
-    // tile and each activation tile from as few places as possible, and so that every XCD ends
-    // on the cheap tiles: 4-bit tiles take about twice as long as 8-bit ones (unpack, per-group
-    // rescale), and the cheap ones fill the last, partly empty round of the grid.
+    // Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Logical ids enumerate
+    // the tile grid in bands of `band` token tiles: inside a band, channel tiles are the outer
+    // index and the band's token tiles the inner one, so the ~64 blocks an XCD runs at a time
+    // form a roughly square patch (band x 64/band tiles) that shares both its activation rows
+    // and its weight columns through that L2.  Every XCD gets a contiguous range of the 4-bit
+    // ids followed by a contiguous range of the 8-bit ids, so that every XCD ends on the cheap
+    // tiles: 4-bit tiles take about twice as long as 8-bit ones (unpack, per-group rescale), and
+    // the cheap ones fill the last, partly empty round of the grid.
     const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
-    int bn, bm;
-    bool part8;
-    if (i < per4) {
-        const int L = xcd * per4 + i;
-        if (L >= nbm * nb4) return;
-        part8 = false;
-        bn = L / nbm;
-        bm = L % nbm;
-    } else {
-        const int L = xcd * per8 + (i - per4);
-        if (L >= nbm * nb8) return;
-        part8 = true;
-        bn = L / nbm;
-        bm = L % nbm;
-    }
+    const bool part8 = i >= per4;
+    const int nb = part8 ? nb8 : nb4;
+    const int L = part8 ? xcd * per8 + (i - per4) : xcd * per4 + i;
+    if (L >= nbm * nb) return;
+    const int bd = L / (band * nb);              // bands before the last one are full
+    const int w = min(band, nbm - bd * band);    // token tiles in this band
+    const int r = L - bd * band * nb;
+    const int bn = r / w, bm = bd * band + r % w;
     constexpr int T16 = C::BN / TILE_N;
     constexpr bool ASYNC = W8PC && ACT_PT && !DUMP;   // the benchmarked variant; spill free (checked by the build)
     if (part8) {
@@ -610,7 +605,7 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
 // the loaded code object of the current device).
 template <typename C, typename K>
 static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStream_t st, const LinearParams &p, int nbm,
-                          int nb8, int nb4, int per4, int per8)
+                          int nb8, int nb4, int per4, int per8, int band)
 {
     const size_t lds_bytes = (size_t)NSTAGE * C::A_STAGE + (with_sa ? (size_t)NSTAGE * C::BM * sizeof(float) : 16);
     // (kernel, device) pairs already configured; a handful of instantiations exist
@@ -633,7 +628,7 @@ static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStre
             if (ndone < 64) done[ndone++] = Done{(const void *)kernel, dev};
         }
     }
-    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm, nb8, nb4, per4, per8);
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm, nb8, nb4, per4, per8, band);
     return (int)hipGetLastError();
 }
 
@@ -645,13 +640,14 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
     const int nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN, nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
     const int per4 = (nbm * nb4 + 7) / 8, per8 = (nbm * nb8 + 7) / 8;
     dim3 grid((per4 + per8) * 8), block(C::THREADS);
+    const int band = p.tune >= 2 ? min(p.tune, nbm) : min(4, nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
     if (p.P)
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, true, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8);
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, true, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     if (p.act_per_token && p.w8_per_channel)
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, true>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8);
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, true>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     if (p.act_per_token)
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8);
-    return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8);
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+    return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
 }
 
 int launch_linear_prefill(const LinearParams &p, hipStream_t st)

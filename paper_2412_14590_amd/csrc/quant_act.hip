@@ -14,22 +14,12 @@ static __device__ inline float wave_max(float v)
     return v;
 }
 
-// fp32 scale -> stored fp16 scale; a scale that is (or rounds to) zero becomes 1.
-static __device__ inline half_t store_scale(float s32)
-{
-    half_t s16 = (half_t)s32;   // round-to-nearest-even conversion
-    if ((float)s16 == 0.0f) s16 = (half_t)1.0f;
-    return s16;
-}
-
 static __device__ inline uint2 quant8(const h8 &v, float s)
 {
     uint32_t w[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        float t = __builtin_rintf((float)v[i] / s);        // IEEE division, ties to even
-        t = fminf(fmaxf(t, -127.0f), 127.0f);
-        w[i >> 2] |= ((uint32_t)(int)t & 0xffu) << (8 * (i & 3));
+        w[i >> 2] |= quant_code(v[i], s) << (8 * (i & 3));
     }
     return make_uint2(w[0], w[1]);
 }

@@ -9,13 +9,6 @@ namespace mixllm {
 
 typedef half_t h8 __attribute__((ext_vector_type(8)));
 
-static __device__ inline half_t store_scale(float s32)
-{
-    half_t s16 = (half_t)s32;
-    if ((float)s16 == 0.0f) s16 = (half_t)1.0f;
-    return s16;
-}
-
 static __device__ inline float block_max_256(float v, float *red)
 {
 #pragma unroll

@@ -39,7 +39,7 @@ def test_query_sizes_matches_the_layout_arithmetic_and_paper_footprints():
     assert s["scales4_bytes"] == n4p * ngp * 2 and s["zeros4_bytes"] == n4p * ngp // 2
     assert s["scales8_bytes"] == n8p * 2 and s["perm_bytes"] == 4 * N
     assert s["xq_bytes"] == 3 * K and s["xscale_bytes"] == 6 and s["y_bytes"] == 3 * N * 2
-    assert s["workspace_bytes"] == 0
+    assert s["workspace_bytes"] == 3 * K + 256      # xq, then xscale, each rounded up to 256 bytes
     # per stored weight the 4-bit part costs 0.5 + 2.5/G bytes and the group-wise 8-bit part
     # 1 + 2/G bytes (Sec. 3.5, memory traffic)
     assert (s["w4_bytes"] + s["scales4_bytes"] + s["zeros4_bytes"]) / (n4p * K) == 0.5 + 2.5 / 128
