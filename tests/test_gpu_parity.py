@@ -282,3 +282,71 @@ def test_llama3_8b_prefill_layers_full_size_sampled_rows(name, M):
     # integer pipeline of the tiled path at full N and K on those rows
     P = mx.debug_group_partials(dev(xq_ref), PL, mx.PATH_PREFILL)
     assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref, L))
+
+
+def _check_layer(lay, Ms_full, Ms_sampled, seed, partial_rows=8):
+    """One full-size layer against the oracle: every row for small M, a seeded sample of token rows
+    (all channels, all groups) for large M; integer partials of the dispatched path on a few rows."""
+    L = ref.quantize_weights(lay.W, lay.salient_idx)
+    PL = mx.quantize_weights(dev(lay.W), lay.salient_idx)
+    for M in Ms_full:
+        x = synth.make_x(M, lay.K, seed=seed + M)
+        xq_ref, xs_ref = ref.quantize_act(x)
+        y = mx.linear_fp16(dev(x), PL)
+        err = row_rel_err(y.cpu().numpy(), ref.mixed_linear(xq_ref, xs_ref, L))
+        say(f"  {lay.name} K={lay.K} N={lay.N} n8={lay.n8} M={M}: row rel err {err:.2e}")
+        assert err <= TOL
+    for M in Ms_sampled:
+        x = synth.make_x(M, lay.K, seed=seed + M)
+        y = mx.linear_fp16(dev(x), PL)
+        rows = np.sort(np.random.default_rng(seed).choice(M, min(M, 16), replace=False))
+        rows[0], rows[-1] = 0, M - 1
+        xq_ref, xs_ref = ref.quantize_act(x[rows])
+        err = row_rel_err(y.cpu().numpy()[rows], ref.mixed_linear(xq_ref, xs_ref, L))
+        say(f"  {lay.name} K={lay.K} N={lay.N} n8={lay.n8} M={M} (sampled rows): row rel err {err:.2e}")
+        assert err <= TOL
+        xs_small = dev(xq_ref[:partial_rows])
+        for path in (mx.PATH_DECODE, mx.PATH_PREFILL):
+            P = mx.debug_group_partials(xs_small, PL, path)
+            assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref[:partial_rows], L))
+
+
+@pytest.mark.parametrize("name,Ms_full,Ms_sampled", [("qkv", (1, 16), (64, 256)), ("o", (1, 16), (256, 2048)),
+                                                    ("gate_up", (1,), (64,)), ("down", (1, 16), (256,))])
+def test_llama31_70b_layers(name, Ms_full, Ms_sampled):
+    # the Llama-3.1-70B-shaped layers of the workload list: N(0, 0.015) weights, N/64 outlier rows
+    K, N = synth.LLAMA31_70B[name]
+    lay = synth.make_layer(name, K, N, sigma=synth.SIGMA["70b"], n_outlier_rows=N // 64, seed=2)
+    say("70B", name, K, N, lay.n8)
+    _check_layer(lay, Ms_full, Ms_sampled, seed=300)
+
+
+def test_llama3_8b_prefill_8192_tokens_sampled_rows():
+    K, N = synth.LLAMA3_8B["o"]
+    lay = synth.make_layer("o", K, N, seed=1)
+    _check_layer(lay, (), (8192,), seed=400)
+
+
+def test_uneven_8bit_share_across_a_32_layer_stack():
+    # per-layer 8-bit shares drawn so that the stack averages 10 % (0 % .. 40 % per layer), plus the
+    # all-4-bit and all-8-bit degenerate layers, at M = 1 and M = 256: the scatter has to put every
+    # channel back in place whatever the split, and no part may be assumed non-empty
+    fr = synth.uneven_fractions(32, seed=0)
+    by_name = {}
+    for (layer, name), f in fr.items():
+        by_name.setdefault(name, []).append((f, layer))
+    total = sum(synth.LLAMA3_8B[n][1] * f for (l, n), f in fr.items()) / sum(synth.LLAMA3_8B[n][1] for (l, n) in fr)
+    assert abs(total - 0.10) < 5e-3 and max(fr.values()) <= 0.40 + 1e-9
+    picks = []
+    for name, lst in by_name.items():
+        lst.sort()
+        picks += [(name, lst[0][0], lst[0][1]), (name, lst[-1][0], lst[-1][1])]    # smallest and largest share
+    picks += [("o", 0.0, 98), ("o", 1.0, 99)]
+    for name, f, layer in picks:
+        if name == "gate_up" and 0.0 < f < 0.3:
+            continue   # the large layer once (its largest share) is enough for the running time
+        K, N = synth.LLAMA3_8B[name]
+        lay = synth.make_layer(name, K, N, frac8=f, seed=1000 + layer)
+        say(f"uneven: layer {layer} {name} share {f:.3f} n8={lay.n8}")
+        assert lay.n8 == synth.n8_for(N, f)
+        _check_layer(lay, (1,), (256,), seed=500 + layer, partial_rows=4)
