@@ -52,8 +52,12 @@ enum {
 enum {
     MIXLLM_PATH_AUTO = 0,    /* decode path for M <= 16, tiled MFMA path otherwise */
     MIXLLM_PATH_GENERIC = 1, /* one thread per output element, no MFMA; any shape; slow */
-    MIXLLM_PATH_DECODE = 2,  /* weight-streaming path, M <= 16 */
-    MIXLLM_PATH_PREFILL = 3  /* LDS-staged tiled MFMA path, any M */
+    MIXLLM_PATH_DECODE = 2,  /* weight-streaming path, M <= 16; picks one of the three variants below */
+    MIXLLM_PATH_PREFILL = 3, /* LDS-staged tiled MFMA path, any M */
+    /* the variants of the decode path, for tests and benchmarks */
+    MIXLLM_PATH_DECODE_STREAM = 4,   /* a wave per tile (or per K part of a tile), activations re-read per tile */
+    MIXLLM_PATH_DECODE_RESIDENT = 5, /* activation fragments kept in registers; falls back to STREAM where it cannot run */
+    MIXLLM_PATH_DECODE_SPLIT = 6     /* equal byte shares per block, activations in LDS; EUNSUPPORTED where it cannot run */
 };
 
 typedef struct mixllm_desc {
@@ -170,10 +174,11 @@ int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xsca
  * fp16 outputs in the original channel order out):
  *   x fp16 [M][K] -> y fp16 [M][N], same definition as mixllm_quantize_activations followed by
  *   mixllm_mixed_linear, with bit-identical results.
- * For M = 1 and K <= 4096 this is ONE kernel: every block of the decode kernel quantizes the
- * activations itself while its first weight loads are in flight, and `workspace` is not
- * touched (may be NULL).  Otherwise the two kernels run back to back on `stream` with xq and
- * xscale placed in `workspace` (at least mixllm_query_sizes().workspace_bytes, 16-byte aligned).
+ * For M = 1 and K <= 4096, or K <= 16384 with one activation scale per token, this is ONE
+ * kernel: every block of the decode kernel quantizes the activations itself while its first
+ * weight loads are in flight, and `workspace` is not touched (may be NULL).  Otherwise the two
+ * kernels run back to back on `stream` with xq and xscale placed in `workspace` (at least
+ * mixllm_query_sizes().workspace_bytes, 16-byte aligned).
  * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP.  M = 0 is a no-op.
  */
 int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *packed_w4,

@@ -16,10 +16,15 @@ LIB_PATH = os.path.join(HERE, "libmixllm_hip.so")
 GROUP = 128
 
 PATH_AUTO, PATH_GENERIC, PATH_DECODE, PATH_PREFILL = 0, 1, 2, 3
+PATH_DECODE_STREAM, PATH_DECODE_RESIDENT, PATH_DECODE_SPLIT = 4, 5, 6
 
 
 class MixllmError(RuntimeError):
-    pass
+    """A call into the library returned a status other than MIXLLM_OK (kept in .status)."""
+
+    def __init__(self, message: str, status: int = 0):
+        super().__init__(message)
+        self.status = status
 
 
 class _Desc(C.Structure):
@@ -68,7 +73,7 @@ def lib():
 
 def _check(rc: int, what: str):
     if rc != 0:
-        raise MixllmError(f"{what}: {lib().mixllm_status_string(rc).decode()} ({rc})")
+        raise MixllmError(f"{what}: {lib().mixllm_status_string(rc).decode()} ({rc})", rc)
 
 
 def abi_version() -> int:
@@ -233,8 +238,8 @@ def linear(x: torch.Tensor, L: PackedLayer, act_group=None, path: int = PATH_AUT
 
 
 def linear_fp16(x: torch.Tensor, L: PackedLayer, act_group=None, out=None, workspace=None) -> torch.Tensor:
-    """fp16 x [M,K] -> fp16 y [M,N] through mixllm_mixed_linear_fp16: one kernel for M = 1 and
-    K <= 4096 (the decode kernel quantizes its own activations), otherwise quantizer + linear with
+    """fp16 x [M,K] -> fp16 y [M,N] through mixllm_mixed_linear_fp16: one kernel for a single token
+    where the decode kernel can quantize its own activations, otherwise quantizer + linear with
     xq / xscale in `workspace` (a uint8 tensor of query_sizes()['workspace_bytes'], allocated here
     when not given)."""
     assert x.dtype == torch.float16 and x.dim() == 2
@@ -243,7 +248,7 @@ def linear_fp16(x: torch.Tensor, L: PackedLayer, act_group=None, out=None, works
     d = L.desc(M, act_group)
     y = torch.empty((M, L.N), dtype=torch.float16, device=x.device) if out is None else out
     need = query_sizes(M, K, L.N, L.n8, act_group, L.w8_group)["workspace_bytes"]
-    if workspace is None and not (M == 1 and K <= 4096):
+    if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     wb = 0 if workspace is None else workspace.numel()
     _check(lib().mixllm_mixed_linear_fp16(C.byref(d), _ptr(x), _ptr(L.w4), _ptr(L.w8), _ptr(L.s4), _ptr(L.s8),

@@ -10,7 +10,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.environ.get("MIXLLM_LIB_OUT", os.path.join(HERE, "libmixllm_hip.so"))
 PROBE_LIB = os.path.join(HERE, "libmixllm_probe.so")
 SOURCES = ["api.hip", "quant_act.hip", "quant_weights.hip", "linear_generic.hip",
-           "linear_decode.hip", "linear_prefill.hip"]
+           "linear_decode.hip", "linear_decode_split.hip", "linear_prefill.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # correctly rounded fp32 division: the quantizers must match IEEE division bit for bit
@@ -48,7 +48,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     by modification time unless force is set."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    deps = [os.path.join(CSRC, "internal.h"), os.path.join(INCLUDE, "mixllm.h"), __file__]
+    deps = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "async_loads.h"), os.path.join(INCLUDE, "mixllm.h"), __file__]
     dep_m = max(os.path.getmtime(p) for p in deps)
     objs, procs = [], []
     for src in SOURCES:

@@ -1,6 +1,7 @@
 // C ABI of libmixllm_hip.so: argument validation (host only, before anything is launched),
 // size accounting, feature permutation, and dispatch to the kernel launchers.
 #include <cstdlib>
+#include <mutex>
 #include <vector>
 
 #include "internal.h"
@@ -75,6 +76,39 @@ LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xsc
     return p;
 }
 
+}  // namespace
+
+namespace mixllm {
+int ensure_dynamic_lds(const void *kernel, size_t bytes)
+{
+    // (kernel, device) pairs already configured with at least this size; a few dozen instantiations exist
+    struct Done {
+        const void *fn;
+        int dev;
+        size_t bytes;
+    };
+    static Done done[256];
+    static int ndone = 0;
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < ndone; ++i)
+        if (done[i].fn == kernel && done[i].dev == dev) {
+            if (done[i].bytes >= bytes) return (int)hipSuccess;
+            hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+            if (e == hipSuccess) done[i].bytes = bytes;
+            return (int)e;
+        }
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return (int)e;
+    if (ndone < 256) done[ndone++] = Done{kernel, dev, bytes};
+    return (int)hipSuccess;
+}
+}  // namespace mixllm
+
+namespace {
+
 int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 
 int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t st)
@@ -87,6 +121,15 @@ int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t 
     case MIXLLM_PATH_DECODE:
         if (d.M > 16) return MIXLLM_EUNSUPPORTED;
         return hip_status(launch_linear_decode(p, st));
+    case MIXLLM_PATH_DECODE_STREAM:
+    case MIXLLM_PATH_DECODE_RESIDENT:
+    case MIXLLM_PATH_DECODE_SPLIT: {
+        if (d.M > 16) return MIXLLM_EUNSUPPORTED;
+        LinearParams q = p;   // the variants are what the tuning override selects
+        q.tune = path == MIXLLM_PATH_DECODE_STREAM ? 999 : path == MIXLLM_PATH_DECODE_RESIDENT ? 1000 : 3000;
+        if (path == MIXLLM_PATH_DECODE_SPLIT && !decode_split_covers(q)) return MIXLLM_EUNSUPPORTED;
+        return hip_status(launch_linear_decode(q, st));
+    }
     case MIXLLM_PATH_PREFILL:
         return hip_status(launch_linear_prefill(p, st));
     default:
@@ -213,7 +256,7 @@ static int linear_common(const mixllm_desc *d, const int8_t *xq, const void *xsc
                          void *stream)
 {
     if (int rc = check_desc(d)) return rc;
-    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_PREFILL) return MIXLLM_EINVAL;
+    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_DECODE_SPLIT) return MIXLLM_EINVAL;
     if (d->M == 0) return MIXLLM_OK;
     mixllm_sizes s;
     sizes_of(*d, s);
@@ -269,7 +312,7 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
     // from three on (its work is repeated by every block).  MIXLLM_TUNE=2000 takes it whenever
     // it is possible (tests of the M = 2..4 code).
     if (decode_can_fuse_quantizer(p) && (d->M == 1 || p.tune == 2000)) {
-        p.tune = 0;
+        if (p.tune == 2000) p.tune = 0;
         p.x = (const half_t *)x;
         return hip_status(launch_linear_decode(p, (hipStream_t)stream));
     }

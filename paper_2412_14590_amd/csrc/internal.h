@@ -112,6 +112,11 @@ int launch_unpack_weights(const mixllm_desc &d, const void *w8, const void *w4, 
                           void *s4c, uint8_t *z4c, hipStream_t st);
 int launch_linear_generic(const LinearParams &p, hipStream_t st);
 int launch_linear_decode(const LinearParams &p, hipStream_t st);
+// evenly split decode variant
+int launch_linear_decode_split(const LinearParams &p, hipStream_t st);
+bool decode_split_covers(const LinearParams &p);
+// Raise a kernel's dynamic-LDS limit (a per-function, per-device attribute; set once).  Returns a hipError_t.
+int ensure_dynamic_lds(const void *kernel, size_t bytes);
 // true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);

@@ -618,16 +618,36 @@ static int try_launch_resident(const LinearParams &p, int blocks_per_cu, hipStre
 // is split WPB ways inside a block when there are too few tiles for that, and a wave takes
 // two tiles when M is large enough for the activation traffic to matter.
 // The resident variant takes fp16 activations when K is a single slab of 8 waves (K <= 4096).
-bool decode_can_fuse_quantizer(const LinearParams &p)
+static bool resident_can_fuse(const LinearParams &p)
 {
     return p.M >= 1 && p.M <= FUSED_MAX_M && p.ng <= 32 && !p.P;
+}
+
+// The evenly split variant streams large layers faster (67 MB of weights: 14.5 us against 16.2;
+// 34 MB with K = 14336: 12.1 against 13.0) and has about 2 us more fixed cost (13 MB: 8.2 us
+// against 6.1), so it takes the layers from 20 MB of weights on.  tune >= 3000 forces it
+// wherever it can run, tune 1..2999 keeps it off (experiments).
+static bool prefer_split(const LinearParams &p)
+{
+    if (p.tune != 0) return p.tune >= 3000;
+    const double bytes = (2.0 * p.ntiles8 + p.ntiles4) * p.ng * 1024.0;
+    return bytes >= 20e6;
+}
+
+// fp16 activations (p.x set on the copy that is tested) can be taken by one of the variants
+bool decode_can_fuse_quantizer(const LinearParams &p)
+{
+    LinearParams q = p;
+    q.x = (const half_t *)(uintptr_t)16;   // only tested against null
+    return resident_can_fuse(p) || (!p.P && decode_split_covers(q));
 }
 
 int launch_linear_decode(const LinearParams &p, hipStream_t st)
 {
     if (p.M == 0 || p.N == 0) return hipSuccess;
-    if (p.x) {   // fused quantizer: resident variant only
-        if (!decode_can_fuse_quantizer(p)) return (int)hipErrorInvalidValue;
+    if (decode_split_covers(p) && (prefer_split(p) || (p.x && !resident_can_fuse(p)))) return launch_linear_decode_split(p, st);
+    if (p.x) {   // fused quantizer
+        if (!resident_can_fuse(p)) return (int)hipErrorInvalidValue;
         const int rc = try_launch_resident<8>(p, 1, st);
         return rc >= 0 ? rc : (int)hipErrorInvalidValue;
     }

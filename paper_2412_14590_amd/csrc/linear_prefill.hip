@@ -30,78 +30,13 @@
 #include <type_traits>
 
 #include "internal.h"
+#include "async_loads.h"
 
 namespace mixllm {
 
 constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
 constexpr int DFRAG = 6;    // an A fragment is requested this many MFMA slots before its use
 constexpr int RING = 8;     // fragment registers (DFRAG + 2: the slot being overwritten is two MFMAs old)
-
-// ---- asynchronous global loads, issued and awaited by hand ---------------------------------
-// Inside the main loops every global load is an `asm volatile`, for two reasons.  (1) The
-// direct-to-LDS load, when the compiler sees it, makes its wait-count bookkeeping fall back to
-// waiting for ALL outstanding memory operations before any later dependent instruction, which
-// serialises the fragment pipeline.  (2) The vector-memory counter retires in order: with the
-// loads hidden in asm the issue order is exactly the program order, so one `s_waitcnt vmcnt(N)`
-// ("all but the youngest N loads of this wave have landed") per group covers everything, and
-// the youngest loads - the activation tile two groups ahead - stay in flight across it.
-// A register filled by such a load is only read after passing through await_*(), which ties
-// the register to the wait.  A wait with N smaller than the number of younger loads merely
-// waits longer; it is never unsafe.
-
-// 16 bytes per lane, global -> LDS: lane l writes lds_base + 16 l.  lds_base is wave uniform.
-static __device__ inline void load_lds16(uint32_t lds_base, uint32_t voff, const void *sbase)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
-}
-template <int OFF>
-static __device__ inline void load_reg16(v4i &dst, uint32_t voff, const void *sbase)
-{
-    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=&v"(dst) : "v"(voff), "s"(sbase), "n"(OFF) : "memory");
-}
-static __device__ inline void load_reg8(uint2 &dst, uint32_t voff, const void *sbase)
-{
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
-}
-static __device__ inline void load_reg_u16(uint32_t &dst, uint32_t voff, const void *sbase)
-{
-    asm volatile("global_load_ushort %0, %1, %2" : "=&v"(dst) : "v"(voff), "s"(sbase) : "memory");
-}
-template <int N>
-static __device__ inline void await_loads(v4i &a, v4i &b)
-{
-    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
-}
-template <int N>
-static __device__ inline void await_loads(v4i &a, v4i &b, v4i &c, v4i &d)
-{
-    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
-}
-template <int N>
-static __device__ inline void await_loads()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-template <int N>
-static __device__ inline void await_loads(uint2 &a, uint32_t &b)
-{
-    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
-}
-// Block-wide barrier in the middle of a group, written out instead of __syncthreads(): the
-// fence of the latter would wait for every outstanding load and LDS read.  The caller has
-// already waited for what must have landed; LDS_WRITES adds this wave's own LDS stores.
-template <bool LDS_WRITES>
-static __device__ inline void mid_group_barrier()
-{
-    if (LDS_WRITES)
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else
-        asm volatile("s_barrier" ::: "memory");
-}
-static __device__ inline uint32_t lds_address(const void *p)
-{
-    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
-}
 
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
 template <int I, int N, typename F>

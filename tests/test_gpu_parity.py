@@ -13,11 +13,29 @@ from util import G, TOL, dev, make_case, pack_from_oracle, row_rel_err
 
 pytestmark = pytest.mark.gpu
 
-PATHS = {"generic": mx.PATH_GENERIC, "decode": mx.PATH_DECODE, "prefill": mx.PATH_PREFILL}
+PATHS = {"generic": mx.PATH_GENERIC, "decode": mx.PATH_DECODE, "prefill": mx.PATH_PREFILL,
+         "decode_stream": mx.PATH_DECODE_STREAM, "decode_resident": mx.PATH_DECODE_RESIDENT,
+         "decode_split": mx.PATH_DECODE_SPLIT}
+DECODE_VARIANTS = ["decode_stream", "decode_resident", "decode_split"]
 
 
 def say(*a):
     print(*a, flush=True)
+
+
+def split_variant_covers(M, K):
+    """The evenly split decode variant stages the whole int8 activation matrix in LDS."""
+    return M <= 16 and M * K <= 65536
+
+
+def skip_unless_covered(path, M, K):
+    if path == "decode_split" and not split_variant_covers(M, K):
+        with pytest.raises(mx.MixllmError) as e:
+            mx.mixed_linear(torch.zeros((M, K), dtype=torch.int8, device="cuda"),
+                            torch.ones((M, 1), dtype=torch.float16, device="cuda"),
+                            pack_from_oracle(make_case(0, K, 16, 0, seed=1)[2]), mx.PATH_DECODE_SPLIT)
+        assert e.value.status == -2     # MIXLLM_EUNSUPPORTED, not a silent fallback
+        pytest.skip("shape outside the split variant")
 
 
 # ------------------------------------------------------------- activation quantizer --
@@ -94,10 +112,11 @@ def check_partials(M, K, N, n8, path, seed=24):
 
 
 @pytest.mark.parametrize("M,K,N,n8", [(3, 256, 7, 2), (16, 1024, 100, 9), (1, 4096, 300, 30), (9, 640, 50, 0),
-                                     (5, 384, 40, 40)])
-@pytest.mark.parametrize("path", ["generic", "decode"])
+                                     (5, 384, 40, 40), (2, 2048, 2070, 207), (4, 14336, 100, 12)])
+@pytest.mark.parametrize("path", ["generic", "decode"] + DECODE_VARIANTS)
 def test_group_partials_bit_exact_small_m(M, K, N, n8, path):
     say("partials", path, M, K, N, n8)
+    skip_unless_covered(path, M, K)
     check_partials(M, K, N, n8, path)
 
 
@@ -148,10 +167,11 @@ def check_linear(M, K, N, n8, path, variant="baseline", seed=25):
 
 
 @pytest.mark.parametrize("variant", ["baseline", "paper"])
-@pytest.mark.parametrize("path", ["generic", "decode"])
+@pytest.mark.parametrize("path", ["generic", "decode"] + DECODE_VARIANTS)
 @pytest.mark.parametrize("M,K,N,n8", [(1, 4096, 4096, 410), (16, 1024, 100, 9), (4, 640, 50, 0), (7, 384, 40, 40),
-                                     (8, 14336, 272, 27)])
+                                     (8, 14336, 272, 27), (3, 128, 33, 3), (2, 2048, 2070, 207), (1, 14336, 1000, 90)])
 def test_linear_small_m(M, K, N, n8, path, variant):
+    skip_unless_covered(path, M, K)
     check_linear(M, K, N, n8, path, variant)
 
 
@@ -178,12 +198,14 @@ def test_auto_dispatch_and_end_to_end_from_fp16():
 @pytest.mark.parametrize("variant", ["baseline", "paper"])
 @pytest.mark.parametrize("M,K,N,n8", [(1, 4096, 4096, 410), (1, 1024, 100, 9), (4, 640, 50, 0), (7, 384, 40, 40),
                                      (16, 4096, 1024, 102), (3, 128, 33, 3), (2, 2048, 2070, 207), (4, 4096, 600, 60),
-                                     (3, 14336, 96, 10), (40, 512, 64, 6)])
+                                     (3, 14336, 96, 10), (40, 512, 64, 6), (1, 14336, 272, 27), (1, 8192, 4100, 400),
+                                     (1, 16384, 48, 5)])
 def test_fused_quantizer_and_linear_from_fp16(M, K, N, n8, variant):
-    # one call from fp16 activations: for M = 1 and K <= 4096 the decode kernel quantizes its own
-    # activations (with MIXLLM_TUNE=2000 in the environment also for M = 2..4: the suite is run
-    # once that way as well); the result must equal the oracle (quantizer + linear) and agree with
-    # the two-call GPU path on the same inputs
+    # one call from fp16 activations: for M = 1 the decode kernel quantizes its own activations
+    # where a variant can (K <= 4096: resident variant; K <= 16384 with per-token scales: split
+    # variant; with MIXLLM_TUNE=2000 in the environment also for M = 2..4: the suite is run once
+    # that way as well); the result must equal the oracle (quantizer + linear) and agree with the
+    # two-call GPU path on the same inputs
     w8g, ag = (None, None) if variant == "baseline" else (128, 128)
     W, sal, L, x, xq, xs = make_case(M, K, N, n8, seed=31, w8_group=w8g, act_group=ag)
     PL = pack_from_oracle(L)
@@ -194,9 +216,9 @@ def test_fused_quantizer_and_linear_from_fp16(M, K, N, n8, variant):
     say(f"  fused fp16 {variant} M={M} K={K} N={N} n8={n8}: row rel err {err:.2e}")
     assert err <= TOL
     y2 = mx.linear(dev(x), PL, act_group=ag)
-    if M <= 4 and K <= 4096:
-        # same decode kernel with and without the built-in quantizer (when the unfused call also
-        # picks the resident variant the outputs are bit-identical; otherwise within tolerance)
+    if M == 1 or (M <= 4 and K <= 4096):
+        # decode kernel with and without the built-in quantizer (when the unfused call picks the
+        # same variant the outputs are bit-identical; otherwise within tolerance)
         assert row_rel_err(y.cpu().numpy(), y2.cpu().numpy().astype(np.float64)) <= 1e-3
     else:
         assert torch.equal(y, y2)
