@@ -623,15 +623,14 @@ static bool resident_can_fuse(const LinearParams &p)
     return p.M >= 1 && p.M <= FUSED_MAX_M && p.ng <= 32 && !p.P;
 }
 
-// The evenly split variant streams large layers faster (67 MB of weights: 14.5 us against 16.2;
-// 34 MB with K = 14336: 12.1 against 13.0) and has about 2 us more fixed cost (13 MB: 8.2 us
-// against 6.1), so it takes the layers from 20 MB of weights on.  tune >= 3000 forces it
-// wherever it can run, tune 1..2999 keeps it off (experiments).
+// The evenly split variant is taken wherever it can run: it streams large layers faster than
+// the two older variants (67 MB of weights, one token: 13.9 us against 16.2; 34 MB with
+// K = 14336: 11.1 against 13.0; 16 tokens: 15.7 against 19.6) and is within 0.3 us of the
+// resident variant on the smallest (8 MB, one token: 6.0 against 5.8; faster from two tokens
+// on).  tune >= 3000 forces it, tune 1..2999 keeps it off (experiments, variant tests).
 static bool prefer_split(const LinearParams &p)
 {
-    if (p.tune != 0) return p.tune >= 3000;
-    const double bytes = (2.0 * p.ntiles8 + p.ntiles4) * p.ng * 1024.0;
-    return bytes >= 20e6;
+    return p.tune == 0 || p.tune >= 3000;
 }
 
 // fp16 activations (p.x set on the copy that is tested) can be taken by one of the variants
