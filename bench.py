@@ -91,12 +91,21 @@ def main():
                 for l in layers]
         return xs_, bufs
 
+    # Order of the linear launches as the GPU executes them (layer indices; a captured graph adds
+    # its launches at every replay).  The decode kernel launches one block per CU whatever the
+    # layer, so a kernel trace of this run needs this list to tell the layers apart.
+    executed, recording = [], [None]
+
+    def note(li):
+        (executed if recording[0] is None else recording[0]).append(li)
+
     def step(i, xs_, bufs):
         ws = copies[i % n_copies]
         for li in range(len(layers)):
             # the whole hot path from fp16 activations: one fused kernel where the library has one
-            # (M = 1, K <= 4096), otherwise activation quantizer + linear
+            # (a single token), otherwise activation quantizer + linear
             mx.linear_fp16(xs_[li], ws[li], out=bufs[li][2], workspace=bufs[li][3])
+            note(li)
 
     def time_steps(M, steps, warmup):
         """Seconds per step.  Decode steps are launch bound when driven from Python (8 ctypes
@@ -112,25 +121,32 @@ def main():
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             graph = torch.cuda.CUDAGraph()
+            recording[0] = []
             with torch.cuda.stream(side):
                 with torch.cuda.graph(graph, stream=side):
                     for i in range(n_copies):
                         step(i, xs_, bufs)
+            captured, recording[0] = recording[0], None
             torch.cuda.current_stream().wait_stream(side)
+
+            def replay_steps():
+                graph.replay()
+                executed.extend(captured)
+
             for rep in range(3):                          # replay check, with eager work in between
                 for b in bufs:
                     b[2].zero_()
-                graph.replay()
+                replay_steps()
                 torch.cuda.synchronize()
                 for e, b in zip(eager, bufs):
                     assert torch.equal(e, b[2]), "HIP graph replay differs from eager launch"
             nrep_w, nrep = max(1, warmup // n_copies), max(1, -(-steps // n_copies))
             for _ in range(nrep_w):
-                graph.replay()
+                replay_steps()
             torch.cuda.synchronize()
             t = time.perf_counter()
             for _ in range(nrep):
-                graph.replay()
+                replay_steps()
             torch.cuda.synchronize()
             return (time.perf_counter() - t) / (nrep * n_copies)
         for i in range(warmup):
@@ -150,26 +166,41 @@ def main():
         has to agree with.  Also returned: the mean over launches that each have their own event
         pair (includes ~2 us of event and launch handling per launch)."""
         xs_, bufs = make_acts(M)
-        xq, xsc, y, _ = bufs[li]
+        xq, xsc, y, ws = bufs[li]
         mx.quantize_activations(xs_[li], out=(xq, xsc))
+
+        def one(i):
+            # the launch the step makes for this layer: for a single token the decode kernel
+            # that quantizes its own activations, otherwise the linear after the quantizer
+            if M == 1:
+                mx.linear_fp16(xs_[li], copies[i % n_copies][li], out=y, workspace=ws)
+            else:
+                mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+            note(li)
+
         for i in range(max(10, reps)):      # warm: clocks settle over tens of milliseconds at large M
-            mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+            one(i)
         torch.cuda.synchronize()
 
         def burst():
             for i in range(reps):
-                mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+                one(i)
 
         replay = burst
         if not args.no_graph:
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             graph = torch.cuda.CUDAGraph()
+            recording[0] = []
             with torch.cuda.stream(side):
                 with torch.cuda.graph(graph, stream=side):
                     burst()
+            captured, recording[0] = recording[0], None
             torch.cuda.current_stream().wait_stream(side)
-            replay = graph.replay
+
+            def replay():
+                graph.replay()
+                executed.extend(captured)
         replay()
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -183,7 +214,7 @@ def main():
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for i, (a, b) in enumerate(evs):
             a.record()
-            mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+            one(i)
             b.record()
         torch.cuda.synchronize()
         ts = np.array([a.elapsed_time(b) for a, b in evs]) * 1e-3
@@ -198,10 +229,12 @@ def main():
     dom = max(range(len(layers)), key=lambda i: layers[i].K * layers[i].N)   # gate_up
 
     def leg(M, steps, warmup, reps):
+        first = len(executed)
         sec = time_steps(M, steps, warmup)
         k_graph, k_pair = time_dominant(M, reps, dom)
+        launches = executed[first:]
         l = layers[dom]
-        out = {"M": M, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9,
+        out = {"M": M, "launches": launches, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9,
                "TOPS": step_ops(M) / sec / 1e12,
                "dominant_kernel": {"layer": l.name, "us_per_launch": k_graph * 1e6,
                                    "us_with_own_event_pair": k_pair * 1e6,
@@ -244,6 +277,19 @@ def main():
         "step_GBps": primary["GBps"], "step_TOPS": primary["TOPS"],
         "roofline": roof,
     }
+    # order of the primary leg's linear launches, run-length encoded: [[layer names of one period], repeats]
+    runs, seq, i = [], primary["launches"], 0
+    period = list(range(len(layers)))
+    while i < len(seq):
+        if seq[i:i + len(period)] == period:
+            pat = period
+        else:
+            pat = [seq[i]]
+        n = 0
+        while seq[i:i + len(pat)] == pat:
+            n, i = n + 1, i + len(pat)
+        runs.append([[layers[j].name for j in pat], n])
+    result["linear_launch_order"] = runs
 
     # ---- measured ceilings of this GPU (context for the published peaks) ----------------------
     if not args.no_extras:
@@ -266,8 +312,10 @@ def main():
         sweep = []
         for M in ([4, 8, 16] if decode_like else [512]):
             sweep.append(leg(M, max(20, args.steps // 4), 5 if decode_like else 40, 50 if decode_like else 30))
-        result["sweep"] = sweep
         other = leg(2048 if decode_like else 1, 40 if decode_like else 100, 40 if decode_like else 3, 30)
+        for extra in sweep + [other]:
+            del extra["launches"]
+        result["sweep"] = sweep
         key = "prefill" if decode_like else "decode"
         if decode_like:
             other["roofline"] = {"bound": "mfma", "achieved": other["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS,
