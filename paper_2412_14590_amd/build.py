@@ -26,21 +26,26 @@ def _hipcc():
             return c
 
 
-def _check_no_scratch(compile_log: str) -> None:
-    """The prefill kernel variant that issues its weight loads by hand (template flags
-    DUMP=0, ACT_PT=1, W8PC=1) must not spill: a register saved to scratch between such a load
-    and its wait would be saved before the data has arrived.  linear_prefill.hip is compiled
-    with -Rpass-analysis=kernel-resource-usage; fail the build if that variant reports scratch."""
-    import re
+# sources with hand-issued loads -> the kernels in them that must not spill
+NO_SPILL = {"linear_prefill.hip": lambda n: "linear_prefill_kernel" in n and "ELb0ELb1ELb1EEEv" in n,
+            "linear_decode_split.hip": lambda n: "linear_decode_split_kernel" in n}
+
+
+def _check_no_scratch(src: str, compile_log: str) -> None:
+    """Kernels that issue their loads by hand (the prefill variant with template flags DUMP=0,
+    ACT_PT=1, W8PC=1; every evenly split decode kernel) must not spill: a register saved to
+    scratch between such a load and its wait would be saved before the data has arrived.  Their
+    sources are compiled with -Rpass-analysis=kernel-resource-usage; fail the build if one of
+    those kernels reports scratch."""
     found = 0
     for m in re.finditer(r"Function Name: (\S+).*?ScratchSize \[bytes/lane\]: (\d+)", compile_log, re.S):
         name, scratch = m.group(1), int(m.group(2))
-        if "linear_prefill_kernel" in name and "ELb0ELb1ELb1EEEv" in name:
+        if NO_SPILL[src](name):
             found += 1
             if scratch != 0:
                 raise RuntimeError(f"{name} spills {scratch} bytes: hand-issued loads are unsafe in it")
     if found == 0:
-        raise RuntimeError("no resource-usage remark for the hand-issued-load prefill kernel")
+        raise RuntimeError(f"no resource-usage remark for the hand-issued-load kernels of {src}")
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -57,7 +62,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         objs.append(o)
         if force or not os.path.exists(o) or os.path.getmtime(o) < max(os.path.getmtime(s), dep_m):
             cmd = [_hipcc(), *FLAGS, "-c", s, "-o", o]
-            if src == "linear_prefill.hip":
+            if src in NO_SPILL:
                 cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
             if verbose:
                 print(" ".join(cmd))
@@ -65,8 +70,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     failed = False
     for src, pr in procs:
         out, _ = pr.communicate()
-        if src == "linear_prefill.hip" and pr.returncode == 0:
-            _check_no_scratch(out)
+        if src in NO_SPILL and pr.returncode == 0:
+            _check_no_scratch(src, out)
             out = "\n".join(l for l in out.splitlines() if "kernel-resource-usage" not in l and not l.lstrip().startswith(("|", "^")) and not re.match(r"\s*\d+ \|", l))
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if pr.returncode != 0:
