@@ -41,12 +41,89 @@ def quant_alg_bytes(K, M):
     return 2 * M * K + M * K + 2 * M
 
 
+def share_sweep(args, torch, mx, synth, dev):
+    """The grid of the paper's single-linear study (Sec. 5.2: K = 4096, N in {4096, 14336},
+    8-bit shares 0 / 10 / 20 / 50 / 100 %, token counts 1..1024), on seeded synthetic weights:
+    time of the whole path from fp16 activations (quantizer + mixed linear), of the linear alone,
+    and of torch's fp16 matmul on the same GPU as the float16 reference of that study.  Every
+    figure is the mean over `reps` launches replayed from a HIP graph, weights rotating over
+    enough copies to stay out of the memory-side cache."""
+    K, rows = 4096, []
+    shares = [0.0, 0.10, 0.20, 0.50, 1.0]
+    Ms = [1, 16, 64, 256, 1024]
+
+    def graph_time(fn, reps):
+        for i in range(min(reps, 8)):
+            fn(i)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for i in range(reps):
+                    fn(i)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(3):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / (3 * reps)
+
+    for N in (4096, 14336):
+        W = torch.from_numpy(synth.make_w(N, K, seed=0, tag=f"w/sweep{N}")).to(dev)
+        n_f16 = max(2, -(-2 * MALL_BYTES // (2 * N * K)))
+        W16 = [W] + [W.clone() for _ in range(n_f16 - 1)]
+        f16_us = {}
+        for M in Ms:
+            x = torch.from_numpy(synth.make_x(M, K, seed=7, tag="x/sweep")).to(dev)
+            y16 = torch.empty((M, N), dtype=torch.float16, device=dev)
+            f16_us[M] = graph_time(lambda i: torch.matmul(x, W16[i % n_f16].t(), out=y16), 40) * 1e6
+        for f in shares:
+            n8 = synth.n8_for(N, f)
+            sal = synth.select_salient(W.cpu().numpy(), n8, seed=0) if 0 < n8 < N else np.arange(n8, dtype=np.int32)
+            L0 = mx.quantize_weights(W, sal)
+            n_c = max(2, -(-2 * MALL_BYTES // L0.weight_bytes()))
+            Ls = [L0] + [L0.clone() for _ in range(n_c - 1)]
+            for M in Ms:
+                x = torch.from_numpy(synth.make_x(M, K, seed=7, tag="x/sweep")).to(dev)
+                xq, xs = mx.quantize_activations(x)
+                y = torch.empty((M, N), dtype=torch.float16, device=dev)
+                ws = torch.empty(mx.query_sizes(M, K, N, n8)["workspace_bytes"], dtype=torch.uint8, device=dev)
+                reps = 60 if M <= 64 else 30
+                t_path = graph_time(lambda i: mx.linear_fp16(x, Ls[i % n_c], out=y, workspace=ws), reps)
+                t_lin = graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], out=y), reps)
+                row = {"N": N, "share8": f, "n8": n8, "M": M, "path_us": t_path * 1e6, "linear_us": t_lin * 1e6,
+                       "torch_fp16_us": f16_us[M], "speedup_vs_fp16": f16_us[M] / (t_path * 1e6),
+                       "linear_GBps": layer_alg_bytes(K, N, n8, M) / t_lin / 1e9,
+                       "linear_TOPS": 2.0 * M * N * K / t_lin / 1e12}
+                rows.append(row)
+                log(f"[sweep] N={N} share={f:.2f} M={M}: path {row['path_us']:.1f} us, linear {row['linear_us']:.1f} us, "
+                    f"fp16 {row['torch_fp16_us']:.1f} us, x{row['speedup_vs_fp16']:.2f}, "
+                    f"{row['linear_GBps']:.0f} GB/s, {row['linear_TOPS']:.0f} TOPS")
+            del Ls
+            torch.cuda.empty_cache()
+    ref_row = next(r for r in rows if r["N"] == 14336 and r["share8"] == 0.10 and r["M"] == 1)
+    return {"metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)", "value": ref_row["linear_GBps"],
+            "unit": "GB/s", "n_gpus": 1, "steps": 60, "warmup": 8, "ms_per_step": ref_row["linear_us"] * 1e-3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+            "config": {"workload": "single linear K=4096, N in {4096, 14336}, 8-bit share 0..100 %, M in {1, 16, 64, 256, 1024}; "
+                                   "value = the linear at N=14336, 10 % 8-bit, M=1"},
+            "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["decode", "prefill"], default="decode")
+    ap.add_argument("--workload", choices=["decode", "prefill", "share-sweep"], default="decode",
+                    help="share-sweep: single linears K=4096, N in {4096, 14336}, 8-bit shares 0..100 %%, M = 1..1024 "
+                         "(the grid of the paper's single-linear study, Sec. 5.2)")
     ap.add_argument("--m", type=int, default=None, help="tokens (default 1 for decode, 2048 for prefill)")
     ap.add_argument("--no-extras", action="store_true", help="primary leg only (for profiling)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
@@ -66,6 +143,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     mx.lib()   # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
+    if args.workload == "share-sweep":
+        print(json.dumps(share_sweep(args, torch, mx, synth, dev)), flush=True)
+        return
     M0 = args.m if args.m is not None else (1 if args.workload == "decode" else 2048)
 
     # ---- inputs (seeded, synthetic, Llama-3-8B shaped) -----------------------------------

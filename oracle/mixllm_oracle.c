@@ -28,6 +28,8 @@
  *     Y = ((W_q - z) x A_q) . s_w . s_a per group (Sec. 3.5), summed over groups.
  *   - scatter: both parts write one output tensor at their own channel indices
  *     (Sec. 3.4).
+ *   - channel salience and the global choice of the 8-bit channels: Sec. 3.2, Eq. 4 and
+ *     Alg. 1 (equal saliences: the earlier channel first).
  *
  * Quantizer arithmetic is IEEE binary32 (true division, rintf under the default
  * round-to-nearest-even mode), inputs widened exactly from fp16; the linear
@@ -284,6 +286,61 @@ void oracle_mixed_linear(const int8_t *xq, const uint16_t *xs, int64_t act_group
             y[m * N + c] = d2h(acc);
         }
     }
+}
+
+/* ---- global precision search (Sec. 3.2) ------------------------------------------------- */
+
+/* Salience of every output channel of one layer for one gradient sample (Eq. 4 with a single
+ * sample d; lines 3-6 of Alg. 1):
+ *     S1[n] = sum_k G[n][k] * (Qdq(W)[n][k] - W[n][k]),    S[n] = | S1[n] + S1[n]^2 / 2 |
+ * where Qdq is the 4-bit group-wise quantizer above followed by its dequantization
+ * (q - z) * s.  The sum runs in double.  salience[n] = (accumulate ? salience[n] : 0) + weight * S[n]:
+ * Eq. 4's mean over the calibration set is one call per sample with weight = 1 / |D|.
+ * s1 (may be NULL) receives S1 of this sample. */
+void oracle_channel_salience(const uint16_t *W, const uint16_t *Gr, int64_t N, int64_t K, int64_t G,
+                             double weight, int accumulate, double *salience, double *s1)
+{
+    int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        uint8_t *q = (uint8_t *)malloc((size_t)K);
+        uint16_t *s = (uint16_t *)malloc((size_t)ng * sizeof(uint16_t));
+        uint8_t *z = (uint8_t *)malloc((size_t)ng);
+        oracle_quantize_w4(W + n * K, 1, K, G, q, s, z);
+        double first = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t g = k / G;
+            double deq = ((double)q[k] - (double)z[g]) * h2d(s[g]);
+            first += h2d(Gr[n * K + k]) * (deq - h2d(W[n * K + k]));
+        }
+        double sal = fabs(first + 0.5 * first * first);
+        if (s1) s1[n] = first;
+        salience[n] = (accumulate ? salience[n] : 0.0) + weight * sal;
+        free(q); free(s); free(z);
+    }
+}
+
+/* Last two lines of Alg. 1: all channels of all layers (saliences concatenated, `total` of
+ * them) sorted by salience, descending; the first T are marked.  The paper does not say how
+ * equal saliences are ordered: the channel that comes first in the concatenation wins. */
+typedef struct { float s; int64_t i; } sal_item;
+static int sal_cmp(const void *a, const void *b)
+{
+    const sal_item *x = (const sal_item *)a, *y = (const sal_item *)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return x->i < y->i ? -1 : (x->i > y->i ? 1 : 0);
+}
+int oracle_select_salient(const float *salience, int64_t total, int64_t T, uint8_t *chosen)
+{
+    if (T < 0 || T > total) return -1;
+    sal_item *it = (sal_item *)malloc((size_t)(total > 0 ? total : 1) * sizeof(sal_item));
+    if (!it) return -2;
+    for (int64_t i = 0; i < total; ++i) { it[i].s = salience[i]; it[i].i = i; chosen[i] = 0; }
+    qsort(it, (size_t)total, sizeof(sal_item), sal_cmp);
+    for (int64_t i = 0; i < T; ++i) chosen[it[i].i] = 1;
+    free(it);
+    return 0;
 }
 
 int oracle_num_threads(void)

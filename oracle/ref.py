@@ -142,3 +142,40 @@ def mixed_linear(xq: np.ndarray, xs: np.ndarray, L: QuantizedLayer, want_f64: bo
                               _p(y), _p(y64) if want_f64 else None)
     y = y.view(np.float16)
     return (y, y64) if want_f64 else y
+
+
+def channel_salience(W: np.ndarray, grads, G: int = 128):
+    """Salience of every output channel of one layer (Sec. 3.2, Eq. 4): the mean over the
+    gradient samples in `grads` (a list of fp16 [N, K] arrays, or one array) of
+    |S1 + S1^2 / 2| with S1 = sum_k g (Qdq(W) - W).  Returns (salience float64 [N],
+    S1 of the last sample float64 [N])."""
+    wb = _h(W)
+    N, K = wb.shape
+    grads = [grads] if isinstance(grads, np.ndarray) else list(grads)
+    sal = np.zeros(N, np.float64)
+    s1 = np.zeros(N, np.float64)
+    for i, g in enumerate(grads):
+        gb = _h(g)
+        assert gb.shape == (N, K)
+        lib().oracle_channel_salience(_p(wb), _p(gb), _i64(N), _i64(K), _i64(G), C.c_double(1.0 / len(grads)),
+                                      C.c_int(1 if i else 0), _p(sal), _p(s1))
+    return sal, s1
+
+
+def select_salient(saliences, T: int):
+    """Alg. 1, last two lines: `saliences` is a list of float32 arrays, one per layer; the T
+    channels with the largest salience over all layers are chosen (equal values: the earlier
+    channel first).  Returns one ascending int32 index array per layer."""
+    flat = np.ascontiguousarray(np.concatenate([np.asarray(s, np.float32).ravel() for s in saliences]) if saliences
+                                else np.zeros(0, np.float32))
+    chosen = np.zeros(flat.size, np.uint8)
+    lib().oracle_select_salient.restype = C.c_int
+    rc = lib().oracle_select_salient(_p(flat), _i64(flat.size), _i64(T), _p(chosen))
+    if rc != 0:
+        raise ValueError("T must lie in [0, total number of channels]")
+    out, o = [], 0
+    for s in saliences:
+        n = np.asarray(s).size
+        out.append(np.nonzero(chosen[o:o + n])[0].astype(np.int32))
+        o += n
+    return out

@@ -349,6 +349,18 @@ def test_llama3_8b_prefill_8192_tokens_sampled_rows():
     _check_layer(lay, (), (8192,), seed=400)
 
 
+@pytest.mark.parametrize("N", [4096, 14336])
+@pytest.mark.parametrize("share", [0.0, 0.20, 0.50, 0.71, 1.0])
+def test_single_linear_8bit_share_sweep(N, share):
+    # the grid of the paper's single-linear study (Sec. 5.2: K = 4096, N in {4096, 14336}, 8-bit shares
+    # up to 100 %; 71 % is the largest per-layer share its appendix reports), 10 % being covered by
+    # the Llama-shaped layer tests: decode (every row) and tiled path (sampled rows, partials)
+    K = 4096
+    lay = synth.make_layer(f"sweep{N}", K, N, frac8=share, seed=77)
+    say(f"share sweep: N={N} share={share} n8={lay.n8}")
+    _check_layer(lay, (1, 16), (1024,), seed=600 + int(100 * share), partial_rows=4)
+
+
 def test_uneven_8bit_share_across_a_32_layer_stack():
     # per-layer 8-bit shares drawn so that the stack averages 10 % (0 % .. 40 % per layer), plus the
     # all-4-bit and all-8-bit degenerate layers, at M = 1 and M = 256: the scatter has to put every

@@ -376,3 +376,72 @@ def test_config0_shape_runs_and_matches_bruteforce_on_sampled_columns():
     Wn = np.linalg.norm(lay.W.astype(np.float32), axis=1)
     top64 = np.argsort(-Wn)[:64]
     assert np.all(np.isin(top64, lay.salient_idx))
+
+
+# ------------------------------------------------ global precision search (Sec. 3.2) --
+
+def _salience_by_hand(W, Gd):
+    """Eq. 4 for one sample, re-derived from the quantizer's codes in plain fp64 numpy."""
+    q, s, z = ref.quantize_w4(W)
+    N, K = W.shape
+    deq = (q.astype(np.float64).reshape(N, K // 128, 128) - z.astype(np.float64)[:, :, None]) * \
+        s.astype(np.float64)[:, :, None]
+    s1 = (Gd.astype(np.float64) * (deq.reshape(N, K) - W.astype(np.float64))).sum(axis=1)
+    return np.abs(s1 + 0.5 * s1 * s1), s1
+
+
+def test_salience_is_zero_when_the_weights_sit_on_the_4bit_grid():
+    # every group holds the 16 levels 0, 0.5, ..., 7.5: quantization reproduces it exactly
+    W = np.tile(np.arange(16, dtype=np.float16) * np.float16(0.5), (3, 16))       # [3, 256]
+    Gd = synth.make_x(3, 256, seed=5, tag="g").astype(np.float16)
+    sal, s1 = ref.channel_salience(W, Gd)
+    assert np.all(s1 == 0) and np.all(sal == 0)
+
+
+def test_salience_closed_form_first_and_second_order_terms():
+    # one group with range [0, 15] (scale 1, zero point 0) and one element at 7.25 -> code 7,
+    # quantization error -0.25; the gradient is non-zero only there
+    W = np.zeros((1, 128), np.float16)
+    W[0, 1], W[0, 2] = 15.0, 7.25
+    for g, s1_want, sal_want in [(1.0, -0.25, 0.21875),      # |-0.25 + 0.03125|
+                                 (8.0, -2.0, 0.0),           # |-2 + 2|: first and second order cancel
+                                 (-8.0, 2.0, 4.0),           # |2 + 2|
+                                 (4.0, -1.0, 0.5)]:          # |-1 + 0.5|
+        Gd = np.zeros((1, 128), np.float16)
+        Gd[0, 2] = g
+        sal, s1 = ref.channel_salience(W, Gd)
+        assert s1[0] == s1_want and sal[0] == sal_want, (g, s1, sal)
+
+
+def test_salience_equals_the_formula_evaluated_by_hand_and_averages_over_samples():
+    W = synth.make_w(37, 512, seed=11, n_outlier_rows=3)
+    g1 = (synth.make_x(37, 512, seed=12, tag="g1") * 0.05).astype(np.float16)
+    g2 = (synth.make_x(37, 512, seed=13, tag="g2") * 5.0).astype(np.float16)     # large: the square term matters
+    for g in (g1, g2):
+        sal, s1 = ref.channel_salience(W, g)
+        want, s1_want = _salience_by_hand(W, g)
+        assert np.allclose(s1, s1_want, rtol=1e-12, atol=1e-15) and np.allclose(sal, want, rtol=1e-12, atol=1e-15)
+    assert np.any(np.abs(_salience_by_hand(W, g2)[1]) > 0.5)
+    both, _ = ref.channel_salience(W, [g1, g2])
+    assert np.allclose(both, 0.5 * (_salience_by_hand(W, g1)[0] + _salience_by_hand(W, g2)[0]), rtol=1e-12)
+    # a channel's salience depends on its own row only
+    p = np.random.default_rng(2).permutation(37)
+    assert np.array_equal(ref.channel_salience(W[p], g1[p])[0], ref.channel_salience(W, g1)[0][p])
+
+
+def test_global_selection_takes_the_top_t_over_all_layers_with_ties_to_the_earlier_channel():
+    rng = np.random.default_rng(9)
+    layers = [rng.integers(0, 6, n).astype(np.float32) * 0.25 for n in (7, 1, 30, 12)]   # many equal values
+    flat = np.concatenate(layers)
+    for T in (0, 1, 5, 17, flat.size):
+        got = ref.select_salient(layers, T)
+        order = sorted(range(flat.size), key=lambda i: (-flat[i], i))[:T]
+        o = 0
+        for lay, idx in zip(layers, got):
+            want = sorted(i - o for i in order if o <= i < o + lay.size)
+            assert idx.tolist() == want
+            o += lay.size
+        assert sum(len(i) for i in got) == T
+    assert [a.tolist() for a in ref.select_salient([np.float32([3, 1, 2]), np.float32([2, 5])], 3)] == [[0, 2], [1]]
+    with pytest.raises(ValueError):
+        ref.select_salient(layers, flat.size + 1)
