@@ -41,6 +41,61 @@ def quant_alg_bytes(K, M):
     return 2 * M * K + M * K + 2 * M
 
 
+def salience_bench(args, torch, mx, synth, dev):
+    """Global precision search (Sec. 3.2) on synthetic (W, G): the salience kernel on the gate+up
+    shaped layer (K = 4096, N = 28672; it reads W and G once: 4 bytes per weight) and the top-T
+    selection over the saliences of a 32-block stack (1.38 M channels, T = 10 %)."""
+    K, N = synth.LLAMA3_8B["gate_up"]
+    W = torch.from_numpy(synth.make_w(N, K, seed=0, tag="w/gate_up")).to(dev)
+    G = (torch.randn((N, K), device=dev, generator=torch.Generator(device=dev).manual_seed(3)) * 0.05).half()
+    sal = mx.channel_salience(W, G)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(5, min(args.steps, 50))
+    for _ in range(3):
+        mx.channel_salience(W, G, out=sal)
+    a.record()
+    for _ in range(reps):
+        mx.channel_salience(W, G, out=sal)
+    b.record()
+    torch.cuda.synchronize()
+    t_sal = a.elapsed_time(b) * 1e-3 / reps
+    bytes_sal = 4.0 * N * K + 4 * N
+    rng = np.random.default_rng(0)
+    stack = [torch.from_numpy(np.exp(rng.standard_normal(n) + rng.standard_normal()).astype(np.float32)).to(dev)
+             for _ in range(32) for n in (6144, 4096, 28672, 4096)]
+    total = sum(int(t.numel()) for t in stack)
+    mx.select_salient(stack, total // 10)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        chosen = mx.select_salient(stack, total // 10)
+    torch.cuda.synchronize()
+    t_sel = (time.perf_counter() - t0) / 5
+    log(f"[salience] gate+up layer: {t_sal * 1e6:.1f} us, {bytes_sal / t_sal / 1e9:.0f} GB/s; selection of {total // 10} of "
+        f"{total} channels over {len(stack)} layers: {t_sel * 1e3:.2f} ms (host call to host result)")
+    result = {"metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)", "value": bytes_sal / t_sal / 1e9,
+              "unit": "GB/s", "n_gpus": 1, "steps": reps, "warmup": 3, "ms_per_step": t_sal * 1e3, "higher_is_better": True,
+              "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "config": {"workload": "global precision search (Sec. 3.2): channel salience of a K=4096, N=28672 layer from "
+                                     "fp16 W and G; value = its algorithmic bytes (4 per weight) / time"},
+              "roofline": {"bound": "hbm", "achieved": bytes_sal / t_sal / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": bytes_sal / t_sal / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                           "kernel": "channel_salience_kernel, K=4096 N=28672"},
+              "selection": {"layers": len(stack), "channels": total, "T": total // 10, "ms": t_sel * 1e3,
+                            "chosen_per_layer_min_max": [min(len(c) for c in chosen), max(len(c) for c in chosen)]}}
+    if not args.no_cpu:
+        from oracle import ref
+        rows = 2048
+        Wh, Gh = W[:rows].cpu().numpy(), G[:rows].cpu().numpy()
+        t1 = time.perf_counter()
+        ref.channel_salience(Wh, Gh)
+        t_cpu = time.perf_counter() - t1
+        result["cpu_baseline"] = {"value": 4.0 * rows * K / t_cpu / 1e9, "unit": "GB/s", "cores": ref.num_threads(),
+                                  "kind": "oracle", "sample": f"the first {rows} channels of the same layer ({t_cpu * 1e3:.0f} ms)"}
+    return result
+
+
 def share_sweep(args, torch, mx, synth, dev):
     """The grid of the paper's single-linear study (Sec. 5.2: K = 4096, N in {4096, 14336},
     8-bit shares 0 / 10 / 20 / 50 / 100 %, token counts 1..1024), on seeded synthetic weights:
@@ -121,9 +176,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["decode", "prefill", "share-sweep"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "share-sweep", "salience"], default="decode",
                     help="share-sweep: single linears K=4096, N in {4096, 14336}, 8-bit shares 0..100 %%, M = 1..1024 "
-                         "(the grid of the paper's single-linear study, Sec. 5.2)")
+                         "(the grid of the paper's single-linear study, Sec. 5.2); salience: the global precision "
+                         "search of Sec. 3.2 (channel salience of the gate+up layer, selection over a 32-block stack)")
     ap.add_argument("--m", type=int, default=None, help="tokens (default 1 for decode, 2048 for prefill)")
     ap.add_argument("--no-extras", action="store_true", help="primary leg only (for profiling)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
@@ -143,6 +199,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     mx.lib()   # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
+    if args.workload == "salience":
+        print(json.dumps(salience_bench(args, torch, mx, synth, dev)), flush=True)
+        return
     if args.workload == "share-sweep":
         print(json.dumps(share_sweep(args, torch, mx, synth, dev)), flush=True)
         return

@@ -194,6 +194,42 @@ int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void 
                              void *stream);
 
 /*
+ * Global precision search, step 1 (Sec. 3.2, Eq. 4; lines 3-6 of Alg. 1): salience of every
+ * output channel of one layer for one gradient sample,
+ *     S1[n] = sum_k G[n][k] * (Qdq(W)[n][k] - W[n][k]),     S[n] = | S1[n] + S1[n]^2 / 2 |,
+ * where Qdq is the 4-bit group-wise quantizer of mixllm_quantize_weights followed by its
+ * dequantization (q - z) * s (the same codes, bit for bit).
+ *   W, G      device, fp16 [N][K] row-major (weights and the loss gradient w.r.t. them), 16-byte aligned
+ *   salience  device, fp32 [N]: salience[n] = (accumulate ? salience[n] : 0) + weight * S[n].
+ *             Eq. 4's mean over the calibration set is one call per sample with weight = 1 / |D|,
+ *             accumulate = 0 for the first sample.
+ * Only d->K, d->N and d->group are read.  Sums run in fp32.  Errors: EINVAL, EUNSUPPORTED, EHIP.
+ */
+int mixllm_channel_salience(const mixllm_desc *d, const void *W, const void *G, float weight,
+                            int accumulate, float *salience, void *stream);
+
+/*
+ * Global precision search, step 2 (last two lines of Alg. 1): of all channels of all layers the
+ * T with the largest salience are the 8-bit ones.  Equal saliences (the paper does not order
+ * them): the channel that comes first in the concatenation is taken first.
+ *   salience        device, fp32 [layer_offsets[L]]: the layers' saliences one after another;
+ *                   every value finite and >= 0
+ *   layer_offsets   HOST, int64 [L + 1], ascending from 0: layer l owns [offsets[l], offsets[l+1]);
+ *                   read before the call returns
+ *   T               0 <= T <= layer_offsets[L] < 2^31
+ *   selected        device, int32 [T]: the chosen channels as indices INSIDE their layer, layer after
+ *                   layer, ascending inside a layer - layer l's slice is what mixllm_quantize_weights
+ *                   takes as salient_idx (after a copy to the host)
+ *   layer_counts    device, int32 [L]: length of every layer's slice (the layer's n8)
+ *   workspace       device, at least mixllm_select_salient_workspace(L) bytes, 16-byte aligned
+ * Errors: EINVAL, EWORKSPACE, EHIP.
+ */
+size_t mixllm_select_salient_workspace(int32_t L);
+int mixllm_select_salient(const float *salience, const int64_t *layer_offsets, int32_t L, int64_t T,
+                          int32_t *selected, int32_t *layer_counts, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
  * Test hook: the exact int32 partial sum of every (token, channel, group), produced by the
  * integer pipeline of the chosen path (same loads, unpacking and MFMA sequence as the
  * linear), written in ORIGINAL channel order:  P int32 [M][N][K/128].

@@ -62,6 +62,12 @@ def lib():
         L.mixllm_mixed_linear_path.argtypes = [C.POINTER(_Desc)] + [_VP] * 10 + [C.c_size_t, C.c_int, _VP]
         L.mixllm_debug_group_partials.argtypes = [C.POINTER(_Desc)] + [_VP] * 6 + [C.c_int, _VP]
         L.mixllm_mixed_linear_fp16.argtypes = [C.POINTER(_Desc)] + [_VP] * 9 + [C.c_size_t, _VP]
+        L.mixllm_channel_salience.argtypes = [C.POINTER(_Desc), _VP, _VP, C.c_float, C.c_int, _VP, _VP]
+        L.mixllm_select_salient_workspace.argtypes = [C.c_int32]
+        L.mixllm_select_salient_workspace.restype = C.c_size_t
+        L.mixllm_select_salient.argtypes = [_VP, _VP, C.c_int32, C.c_int64, _VP, _VP, _VP, C.c_size_t, _VP]
+        L.mixllm_channel_salience.restype = C.c_int
+        L.mixllm_select_salient.restype = C.c_int
         for name in ("mixllm_query_sizes", "mixllm_build_feature_perm", "mixllm_quantize_weights",
                      "mixllm_pack_weights", "mixllm_unpack_weights", "mixllm_quantize_activations",
                      "mixllm_mixed_linear", "mixllm_mixed_linear_path", "mixllm_debug_group_partials",
@@ -255,3 +261,40 @@ def linear_fp16(x: torch.Tensor, L: PackedLayer, act_group=None, out=None, works
                                           _ptr(L.z4), _ptr(L.perm), _ptr(y), _ptr(workspace), wb, _stream()),
            "mixllm_mixed_linear_fp16")
     return y
+
+
+def channel_salience(W: torch.Tensor, G: torch.Tensor, out=None, weight: float = 1.0, accumulate: bool = False) -> torch.Tensor:
+    """Salience of every output channel of one layer for one gradient sample (fp16 W, G [N,K] ->
+    fp32 [N]); with `out`, weight and accumulate the mean over several samples is built call by call."""
+    assert W.dtype == torch.float16 and G.dtype == torch.float16 and W.shape == G.shape and W.dim() == 2
+    N, K = W.shape
+    W, G = W.contiguous(), G.contiguous()
+    sal = torch.empty(N, dtype=torch.float32, device=W.device) if out is None else out
+    assert sal.dtype == torch.float32 and sal.numel() == N
+    d = _desc(0, K, N, 0, None, None)
+    _check(lib().mixllm_channel_salience(C.byref(d), _ptr(W), _ptr(G), C.c_float(weight), int(bool(accumulate)),
+                                         _ptr(sal), _stream()), "mixllm_channel_salience")
+    return sal
+
+
+def select_salient(saliences, T: int):
+    """The T most salient channels over all layers: `saliences` is a list of fp32 device tensors (one
+    per layer); returns one ascending int32 index tensor per layer (on the device) - the salient_idx
+    of quantize_weights for that layer."""
+    sizes = [int(s.numel()) for s in saliences]
+    flat = torch.cat([s.reshape(-1).to(torch.float32) for s in saliences]) if len(saliences) > 1 else \
+        saliences[0].reshape(-1).to(torch.float32).contiguous()
+    L = len(sizes)
+    offsets = (C.c_int64 * (L + 1))(*np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64).tolist())
+    selected = torch.empty(max(int(T), 1), dtype=torch.int32, device=flat.device)
+    counts = torch.empty(L, dtype=torch.int32, device=flat.device)
+    need = int(lib().mixllm_select_salient_workspace(L))
+    ws = torch.empty(need, dtype=torch.uint8, device=flat.device)
+    _check(lib().mixllm_select_salient(_ptr(flat), C.cast(offsets, _VP), L, int(T), _ptr(selected), _ptr(counts),
+                                       _ptr(ws), need, _stream()), "mixllm_select_salient")
+    cnt = counts.cpu().tolist()
+    out, o = [], 0
+    for c in cnt:
+        out.append(selected[o:o + c])
+        o += c
+    return out

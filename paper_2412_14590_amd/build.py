@@ -10,7 +10,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.environ.get("MIXLLM_LIB_OUT", os.path.join(HERE, "libmixllm_hip.so"))
 PROBE_LIB = os.path.join(HERE, "libmixllm_probe.so")
 SOURCES = ["api.hip", "quant_act.hip", "quant_weights.hip", "linear_generic.hip",
-           "linear_decode.hip", "linear_decode_split.hip", "linear_prefill.hip"]
+           "linear_decode.hip", "linear_decode_split.hip", "linear_prefill.hip", "salience.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # correctly rounded fp32 division: the quantizers must match IEEE division bit for bit

@@ -327,6 +327,36 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
     return dispatch(*d, p, MIXLLM_PATH_AUTO, (hipStream_t)stream);
 }
 
+int mixllm_channel_salience(const mixllm_desc *d, const void *W, const void *G, float weight, int accumulate,
+                            float *salience, void *stream)
+{
+    if (!d) return MIXLLM_EINVAL;
+    if (d->K <= 0 || d->N < 0) return MIXLLM_EINVAL;
+    if (d->group != MIXLLM_GROUP || d->K % MIXLLM_GROUP != 0) return MIXLLM_EUNSUPPORTED;
+    if (d->N == 0) return MIXLLM_OK;
+    if (!W || !G || !salience || !aligned16(W) || !aligned16(G)) return MIXLLM_EINVAL;
+    return hip_status(mixllm::launch_channel_salience(W, G, d->N, d->K, weight, accumulate, salience,
+                                                      (hipStream_t)stream));
+}
+
+size_t mixllm_select_salient_workspace(int32_t L) { return L > 0 ? mixllm::select_salient_workspace_bytes(L) : 0; }
+
+int mixllm_select_salient(const float *salience, const int64_t *layer_offsets, int32_t L, int64_t T,
+                          int32_t *selected, int32_t *layer_counts, void *workspace, size_t workspace_bytes,
+                          void *stream)
+{
+    if (L <= 0 || !layer_offsets || layer_offsets[0] != 0) return MIXLLM_EINVAL;
+    for (int l = 0; l < L; ++l)
+        if (layer_offsets[l + 1] < layer_offsets[l]) return MIXLLM_EINVAL;
+    const int64_t total = layer_offsets[L];
+    if (total >= (1ll << 31) || T < 0 || T > total) return MIXLLM_EINVAL;
+    if (!layer_counts || (total > 0 && !salience) || (T > 0 && !selected)) return MIXLLM_EINVAL;
+    if (!workspace || !aligned16(workspace)) return MIXLLM_EINVAL;
+    if (workspace_bytes < mixllm::select_salient_workspace_bytes(L)) return MIXLLM_EWORKSPACE;
+    return hip_status(mixllm::launch_select_salient(salience, layer_offsets, L, T, selected, layer_counts, workspace,
+                                                    (hipStream_t)stream));
+}
+
 int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const void *packed_w4,
                                 const void *packed_w8, const void *zeros4, const int32_t *feature_perm,
                                 int32_t *P, int path, void *stream)

@@ -120,5 +120,11 @@ int ensure_dynamic_lds(const void *kernel, size_t bytes);
 // true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);
+// global precision search (salience.hip)
+int launch_channel_salience(const void *W, const void *Gr, int N, int K, float weight, int accumulate, float *salience,
+                            hipStream_t st);
+size_t select_salient_workspace_bytes(int L);
+int launch_select_salient(const float *salience, const int64_t *layer_offsets_host, int L, int64_t T, int32_t *selected,
+                          int32_t *layer_counts, void *workspace, hipStream_t st);
 
 }  // namespace mixllm

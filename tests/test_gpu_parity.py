@@ -384,3 +384,89 @@ def test_uneven_8bit_share_across_a_32_layer_stack():
         say(f"uneven: layer {layer} {name} share {f:.3f} n8={lay.n8}")
         assert lay.n8 == synth.n8_for(N, f)
         _check_layer(lay, (1,), (256,), seed=500 + layer, partial_rows=4)
+
+
+# ------------------------------------------------- global precision search (Sec. 3.2) --
+
+def make_grad(N, K, seed, scale):
+    """A stand-in for the loss gradient w.r.t. a layer's weights (the paper's comes from a model and
+    calibration data): N(0, scale) with the same outlier input channels as the activations."""
+    return (synth.make_x(N, K, seed=seed, tag="grad").astype(np.float32) * scale).astype(np.float16)
+
+
+@pytest.mark.parametrize("N,K,scale", [(37, 512, 0.05), (100, 128, 3.0), (4096, 4096, 0.02), (1000, 14336, 0.5),
+                                       (16, 640, 1.0)])
+def test_channel_salience_matches_the_oracle(N, K, scale):
+    say("salience", N, K, scale)
+    W = synth.make_w(N, K, seed=41, n_outlier_rows=min(N, 8))
+    g1, g2 = make_grad(N, K, 42, scale), make_grad(N, K, 43, 2 * scale)
+    ref_one, s1 = ref.channel_salience(W, g1)
+    got = mx.channel_salience(dev(W), dev(g1)).cpu().numpy().astype(np.float64)
+    # fp32 sums against the fp64 definition: the error of S1 is bounded by the rounding of a K-term
+    # fp32 sum of |g| |quantize(W) - W|; S = |S1 + S1^2/2| amplifies it by |1 + S1|
+    q, s, z = ref.quantize_w4(W)
+    deq = (q.astype(np.float64).reshape(N, K // G, G) - z.astype(np.float64)[:, :, None]) * s.astype(np.float64)[:, :, None]
+    mag = (np.abs(g1.astype(np.float64)) * np.abs(deq.reshape(N, K) - W.astype(np.float64))).sum(axis=1)
+    tol = 2e-6 * mag * (1 + np.abs(s1)) + 1e-30
+    assert np.all(np.abs(got - ref_one) <= tol), float(np.max(np.abs(got - ref_one) / tol))
+    # the mean over two samples, built call by call
+    ref_two, _ = ref.channel_salience(W, [g1, g2])
+    acc = mx.channel_salience(dev(W), dev(g1), weight=0.5)
+    mx.channel_salience(dev(W), dev(g2), out=acc, weight=0.5, accumulate=True)
+    assert np.allclose(acc.cpu().numpy(), ref_two, rtol=2e-4, atol=1e-12)
+
+
+def test_channel_salience_uses_the_weight_quantizers_codes():
+    # weights on the 4-bit grid: zero salience whatever the gradient; and the closed form where the
+    # first- and second-order terms cancel (S1 = -2)
+    W = np.tile(np.arange(16, dtype=np.float16) * np.float16(0.5), (3, 16))
+    assert torch.all(mx.channel_salience(dev(W), dev(make_grad(3, 256, 5, 1.0))) == 0)
+    W = np.zeros((2, 128), np.float16)
+    W[:, 1], W[:, 2] = 15.0, 7.25
+    Gd = np.zeros((2, 128), np.float16)
+    Gd[0, 2], Gd[1, 2] = 8.0, -8.0
+    assert mx.channel_salience(dev(W), dev(Gd)).cpu().tolist() == [0.0, 4.0]
+
+
+@pytest.mark.parametrize("case", ["ties", "random", "llama_stack"])
+def test_global_selection_matches_the_oracle_exactly(case):
+    rng = np.random.default_rng(17)
+    if case == "ties":
+        layers = [rng.integers(0, 5, n).astype(np.float32) * 0.125 for n in (7, 1, 300, 4096, 12, 1025)]
+    elif case == "random":
+        layers = [np.abs(rng.standard_normal(n)).astype(np.float32) * 10.0 ** rng.integers(-6, 3) for n in (6144, 4096, 28672, 4096)]
+    else:   # 32 blocks of Llama-3-8B-shaped layers, lognormal saliences whose scale differs per layer
+        layers = [np.exp(rng.standard_normal(n) + rng.standard_normal()).astype(np.float32)
+                  for _ in range(32) for n in (6144, 4096, 28672, 4096)]
+    total = sum(l.size for l in layers)
+    dl = [dev(l) for l in layers]
+    for T in sorted({0, 1, total // 10, total // 2 + 1, total - 1, total}):
+        want = ref.select_salient(layers, T)
+        got = mx.select_salient(dl, T)
+        assert len(got) == len(want)
+        for a, b in zip(got, want):
+            assert np.array_equal(a.cpu().numpy(), b), (case, T)
+    say(f"selection {case}: {len(layers)} layers, {total} channels")
+
+
+def test_precision_search_end_to_end_feeds_the_linear():
+    # Alg. 1 on three synthetic layers, then the chosen channels go into the weight quantizer and the
+    # linear is checked against the oracle run with the same choice
+    shapes = [(512, 96), (1024, 272), (512, 530)]
+    Ws = [synth.make_w(N, K, seed=50 + i, n_outlier_rows=6) for i, (K, N) in enumerate(shapes)]
+    Gs = [make_grad(N, K, 60 + i, 0.3) for i, (K, N) in enumerate(shapes)]
+    sal = [mx.channel_salience(dev(W), dev(Gd)) for W, Gd in zip(Ws, Gs)]
+    T = round(0.10 * sum(N for _, N in shapes))
+    chosen = mx.select_salient(sal, T)
+    want = ref.select_salient([s.cpu().numpy() for s in sal], T)     # same fp32 saliences: same decision
+    assert sum(len(c) for c in chosen) == T
+    for (K, N), W, idx, idx_ref in zip(shapes, Ws, chosen, want):
+        idx = idx.cpu().numpy()
+        assert np.array_equal(idx, idx_ref)
+        L = ref.quantize_weights(W, idx)
+        PL = mx.quantize_weights(dev(W), idx)
+        x = synth.make_x(5, K, seed=70)
+        xq, xs = ref.quantize_act(x)
+        y = mx.linear(dev(x), PL)
+        assert row_rel_err(y.cpu().numpy(), ref.mixed_linear(xq, xs, L)) <= TOL
+    say("precision search: 8-bit channels per layer", [len(c) for c in chosen])

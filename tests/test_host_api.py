@@ -82,6 +82,34 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert L.mixllm_status_string(-2).decode().startswith("unsupported")
 
 
+def test_precision_search_calls_validate_on_the_host():
+    L = mx.lib()
+    d = binding._desc(0, 256, 8, 0)
+    buf = (C.c_uint8 * 8192)()
+    addr = (C.addressof(buf) + 15) & ~15                       # 16-byte aligned host address: never dereferenced
+    vp = C.c_void_p
+    # salience: null / misaligned pointers, K not a multiple of the group
+    assert L.mixllm_channel_salience(C.byref(d), None, vp(addr), C.c_float(1), 0, vp(addr), None) == -1
+    assert L.mixllm_channel_salience(C.byref(d), vp(addr + 2), vp(addr), C.c_float(1), 0, vp(addr), None) == -1
+    bad = binding._desc(0, 200, 8, 0)
+    assert L.mixllm_channel_salience(C.byref(bad), vp(addr), vp(addr), C.c_float(1), 0, vp(addr), None) == -2
+    empty = binding._desc(0, 256, 0, 0)
+    assert L.mixllm_channel_salience(C.byref(empty), None, None, C.c_float(1), 0, None, None) == 0
+    # selection: layer list, T, workspace
+    off = (C.c_int64 * 3)(0, 5, 9)
+    need = L.mixllm_select_salient_workspace(2)
+    assert need > 0 and L.mixllm_select_salient_workspace(0) == 0
+    args = lambda o, nl, T, ws, wb: L.mixllm_select_salient(vp(addr), C.cast(o, vp), nl, C.c_int64(T), vp(addr), vp(addr),
+                                                            ws, C.c_size_t(wb), None)
+    assert args(off, 0, 1, vp(addr), need) == -1                 # no layers
+    assert args(off, 2, 10, vp(addr), need) == -1                # T beyond the number of channels
+    assert args(off, 2, -1, vp(addr), need) == -1
+    assert args((C.c_int64 * 3)(0, 5, 4), 2, 1, vp(addr), need) == -1      # offsets not ascending
+    assert args((C.c_int64 * 3)(1, 5, 9), 2, 1, vp(addr), need) == -1      # offsets do not start at 0
+    assert args(off, 2, 3, None, need) == -1
+    assert args(off, 2, 3, vp(addr), need - 1) == -3             # MIXLLM_EWORKSPACE
+
+
 def test_feature_perm_matches_oracle_and_rejects_bad_lists():
     rng = np.random.default_rng(0)
     for N, n8 in ((8, 3), (100, 0), (100, 100), (4096, 410)):
