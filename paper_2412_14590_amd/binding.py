@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libmixllm_hip.so")
 GROUP = 128
 
 PATH_AUTO, PATH_GENERIC, PATH_DECODE, PATH_PREFILL = 0, 1, 2, 3
-PATH_DECODE_STREAM, PATH_DECODE_RESIDENT, PATH_DECODE_SPLIT = 4, 5, 6
+PATH_DECODE_STREAM, PATH_DECODE_RESIDENT, PATH_DECODE_SPLIT, PATH_MID = 4, 5, 6, 7
 
 
 class MixllmError(RuntimeError):

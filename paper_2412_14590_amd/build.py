@@ -10,7 +10,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.environ.get("MIXLLM_LIB_OUT", os.path.join(HERE, "libmixllm_hip.so"))
 PROBE_LIB = os.path.join(HERE, "libmixllm_probe.so")
 SOURCES = ["api.hip", "quant_act.hip", "quant_weights.hip", "linear_generic.hip",
-           "linear_decode.hip", "linear_decode_split.hip", "linear_prefill.hip", "salience.hip"]
+           "linear_decode.hip", "linear_decode_split.hip", "linear_mid.hip", "linear_prefill.hip", "salience.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # correctly rounded fp32 division: the quantizers must match IEEE division bit for bit
@@ -28,7 +28,8 @@ def _hipcc():
 
 # sources with hand-issued loads -> the kernels in them that must not spill
 NO_SPILL = {"linear_prefill.hip": lambda n: "linear_prefill_kernel" in n and "ELb0ELb1ELb1EEEv" in n,
-            "linear_decode_split.hip": lambda n: "linear_decode_split_kernel" in n}
+            "linear_decode_split.hip": lambda n: "linear_decode_split_kernel" in n,
+            "linear_mid.hip": lambda n: "linear_mid_kernel" in n}
 
 
 def _check_no_scratch(src: str, compile_log: str) -> None:

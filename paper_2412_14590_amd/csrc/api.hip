@@ -113,7 +113,8 @@ int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 
 int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t st)
 {
-    if (path == MIXLLM_PATH_AUTO) path = d.M <= 16 ? MIXLLM_PATH_DECODE : MIXLLM_PATH_PREFILL;
+    if (path == MIXLLM_PATH_AUTO)
+        path = d.M <= 16 ? MIXLLM_PATH_DECODE : (d.M <= 64 && mid_covers(p)) ? MIXLLM_PATH_MID : MIXLLM_PATH_PREFILL;
     switch (path) {
     case MIXLLM_PATH_GENERIC:
         if (d.M > 65535) return MIXLLM_EUNSUPPORTED;
@@ -130,6 +131,9 @@ int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t 
         if (path == MIXLLM_PATH_DECODE_SPLIT && !decode_split_covers(q)) return MIXLLM_EUNSUPPORTED;
         return hip_status(launch_linear_decode(q, st));
     }
+    case MIXLLM_PATH_MID:
+        if (!mid_covers(p)) return MIXLLM_EUNSUPPORTED;
+        return hip_status(launch_linear_mid(p, st));
     case MIXLLM_PATH_PREFILL:
         return hip_status(launch_linear_prefill(p, st));
     default:
@@ -256,7 +260,7 @@ static int linear_common(const mixllm_desc *d, const int8_t *xq, const void *xsc
                          void *stream)
 {
     if (int rc = check_desc(d)) return rc;
-    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_DECODE_SPLIT) return MIXLLM_EINVAL;
+    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_MID) return MIXLLM_EINVAL;
     if (d->M == 0) return MIXLLM_OK;
     mixllm_sizes s;
     sizes_of(*d, s);

@@ -78,4 +78,14 @@ static __device__ inline uint32_t lds_address(const void *p)
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
 }
 
+// fp16 bit pattern (low 16 bits) -> float.  Values that come out of a hand-issued load are taken
+// apart with integer operations and this function only: a reinterpreting copy of the loaded
+// variable itself (memcpy to an array of halves, a union) makes the compiler keep the variable
+// as 16-bit pieces, and it then splits the register right after the load is issued - before the
+// data has arrived - and reassembles it for the wait.
+static __device__ inline float half_bits_to_float(uint32_t bits)
+{
+    return (float)__builtin_bit_cast(half_t, (uint16_t)bits);
+}
+
 }  // namespace mixllm

@@ -120,6 +120,9 @@ int ensure_dynamic_lds(const void *kernel, size_t bytes);
 // true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);
+// path for 17..128 tokens (linear_mid.hip)
+bool mid_covers(const LinearParams &p);
+int launch_linear_mid(const LinearParams &p, hipStream_t st);
 // global precision search (salience.hip)
 int launch_channel_salience(const void *W, const void *Gr, int N, int K, float weight, int accumulate, float *salience,
                             hipStream_t st);

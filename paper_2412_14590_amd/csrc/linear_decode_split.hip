@@ -101,14 +101,6 @@ __device__ inline void await_vec(v4i &a)
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
 }
 
-__device__ inline float half_bits_to_float(uint32_t bits)
-{
-    const uint16_t b = (uint16_t)bits;
-    half_t h;
-    __builtin_memcpy(&h, &b, 2);
-    return (float)h;
-}
-
 template <int NR, bool DUMP, bool ACT_PT, bool PART8, bool FUSED>
 __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, uint8_t *smem)
 {
@@ -285,8 +277,11 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     auto compute = [&](int i, const Slot<PART8> &k) {
         const int j = wave + NW * i;
         const int vt = vtile_of(j), q = j - vt * nquads;
-        half_t sh[4];
-        __builtin_memcpy(sh, &k.s, 8);
+        // The four fp16 scales are taken out of the two loaded dwords with integer operations
+        // only: a reinterpreting copy of k.s makes the compiler keep k.s as 16-bit pieces, and
+        // it then splits the dwords right after the load is issued, before the data is there.
+        const float sh[4] = {half_bits_to_float(k.s.x & 0xffffu), half_bits_to_float(k.s.x >> 16),
+                             half_bits_to_float(k.s.y & 0xffffu), half_bits_to_float(k.s.y >> 16)};
         const float sw_row = (PART8 && !DUMP) ? half_bits_to_float(k.z) : 0.0f;
         int ch = -1;
         if (DUMP) {
@@ -309,7 +304,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
             if (PART8) {
                 P = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, k.w[u][0], v4i{0, 0, 0, 0}, 0, 0, 0);
                 P = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, k.w[u][PART8 ? 1 : 0], P, 0, 0, 0);
-                sw = per_group_s8 ? (float)sh[u] : sw_row;
+                sw = per_group_s8 ? sh[u] : sw_row;
             } else {
                 const v4i w = k.w[u][0];
                 const int m4 = 0x0F0F0F0F;
@@ -323,7 +318,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
                 // |z| <= 15 and |sum a| <= 128 * 127: the 24-bit multiply is exact
 #pragma unroll
                 for (int r = 0; r < NR; ++r) P[r] -= __mul24(z, S[r]);
-                sw = (float)sh[u];
+                sw = sh[u];
             }
             if (!gvalid) sw = 0.0f;   // a clamped re-read past the end of K contributes nothing
             if (DUMP) {

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 PATHS = {"generic": mx.PATH_GENERIC, "decode": mx.PATH_DECODE, "prefill": mx.PATH_PREFILL,
          "decode_stream": mx.PATH_DECODE_STREAM, "decode_resident": mx.PATH_DECODE_RESIDENT,
-         "decode_split": mx.PATH_DECODE_SPLIT}
+         "decode_split": mx.PATH_DECODE_SPLIT, "mid": mx.PATH_MID}
 DECODE_VARIANTS = ["decode_stream", "decode_resident", "decode_split"]
 
 
@@ -181,6 +181,27 @@ def test_linear_small_m(M, K, N, n8, path, variant):
                                      (512, 4096, 1024, 102)])
 def test_linear_tiled(M, K, N, n8, path, variant):
     check_linear(M, K, N, n8, path, variant)
+
+
+@pytest.mark.parametrize("M,K,N,n8", [(17, 256, 7, 2), (33, 384, 70, 70), (64, 1024, 530, 0), (50, 640, 50, 5),
+                                     (64, 512, 300, 30), (20, 4096, 1000, 100), (64, 14336, 272, 27), (1, 512, 96, 9),
+                                     (48, 2048, 2070, 207)])
+def test_mid_path_partials_and_linear(M, K, N, n8):
+    # the path for a few dozen tokens: integer partials bit-exact, outputs within tolerance
+    say("mid", M, K, N, n8)
+    check_partials(M, K, N, n8, "mid")
+    check_linear(M, K, N, n8, "mid")
+
+
+def test_mid_path_rejects_what_it_does_not_cover():
+    _, _, L, _, xq, xs = make_case(65, 256, 40, 4, seed=3)
+    with pytest.raises(mx.MixllmError) as e:
+        mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), mx.PATH_MID)       # more than 64 tokens
+    assert e.value.status == -2
+    _, _, L, _, xq, xs = make_case(40, 256, 40, 4, seed=3, w8_group=128, act_group=128)
+    with pytest.raises(mx.MixllmError) as e:
+        mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), mx.PATH_MID)       # group-wise scales
+    assert e.value.status == -2
 
 
 def test_auto_dispatch_and_end_to_end_from_fp16():
