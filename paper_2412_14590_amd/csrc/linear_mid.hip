@@ -3,9 +3,8 @@
 // few for the tiled kernel (its 128 x 128 block tiles leave most CUs idle and its K loop is
 // serial per block: ~25 us on any layer of K = 4096).
 //  * Work is dealt as in the evenly split decode variant: a block takes an equal share of the
-//    quarter tiles (4 channels x all of K) of one precision; `qv` consecutive quarter tiles
-//    (4, 2 or 1: as many as still give every wave a tile) form the 16-column virtual tile of one
-//    wave, and a wave owns its virtual tile for all of K: its accumulators (MT token tiles of
+//    quarter tiles (4 channels x all of K) of one precision; 4 consecutive quarter tiles form
+//    the 16-column virtual tile of one wave (the last one of a share may be partly filled), and a wave owns its virtual tile for all of K: its accumulators (MT token tiles of
 //    16 x 16) stay in registers, nothing is reduced between waves.  A block with more than 8
 //    virtual tiles walks K once per round of 8.
 //  * The loop runs over K in steps of 4 groups (512 k).  The int8 activations of a step, M x 512
@@ -314,14 +313,10 @@ int cu_count()
     return n[dev];
 }
 
-// quarter tiles per virtual tile: the fewest rounds of 8 virtual tiles, then the most busy waves
-int pick_qv(int share)
-{
-    int best_q = 4;
-    for (int q = 2; q >= 1; q /= 2)
-        if (ceil_div(ceil_div(share, q), NW) <= ceil_div(ceil_div(share, best_q), NW)) best_q = q;
-    return best_q;
-}
+// Quarter tiles per virtual tile.  A wave's time per K step does not depend on how many of its 16
+// columns are in use, and two waves on one SIMD take turns, so fewer, fuller virtual tiles are
+// never slower: always 4.
+int pick_qv(int) { return 4; }
 
 // rounds of 8 virtual tiles a block of this share walks K for
 int rounds_of(int share) { return ceil_div(ceil_div(share, pick_qv(share)), NW); }
