@@ -229,8 +229,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
 #pragma unroll
         for (int j = 0; j < MAXV; ++j) {
             if (j * NT < npiece && tid + NT * j < npiece) {
-                h8 hv;
-                __builtin_memcpy(&hv, &xv[j], 16);
+                const h8 hv = __builtin_bit_cast(h8, xv[j]);   // the whole register, after its wait
 #pragma unroll
                 for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf((float)hv[e]));
             }
@@ -247,8 +246,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
         for (int j = 0; j < MAXV; ++j) {
             const int i = tid + NT * j;
             if (j * NT < npiece && i < npiece) {
-                h8 hv;
-                __builtin_memcpy(&hv, &xv[j], 16);
+                const h8 hv = __builtin_bit_cast(h8, xv[j]);   // the whole register, after its wait
                 uint32_t w0 = 0, w1 = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {

@@ -172,10 +172,9 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
             }
         }
     };
-    auto scale_of = [&](const Meta &mt, int u) -> float {
-        half_t hs[4];
-        __builtin_memcpy(hs, &mt.s, 8);
-        return (float)hs[u];
+    auto scale_of = [&](const Meta &mt, int u) -> float {   // integer operations only, see half_bits_to_float
+        const uint32_t d = (u & 2) ? mt.s.y : mt.s.x;
+        return half_bits_to_float((u & 1) ? d >> 16 : d & 0xffffu);
     };
     // one eighth of the unpack of a group: raw dword d of `set` -> two operand dwords
     auto unpack_piece = [&](auto setc, auto dc, uint32_t zb) {
