@@ -251,7 +251,7 @@ def main():
         calls of ~5 us each), so n_copies consecutive steps (one per weight copy) are captured
         into one HIP graph and replayed; the graph's output is checked against eager once."""
         xs_, bufs = make_acts(M)
-        use_graph = not args.no_graph and M <= 16
+        use_graph = not args.no_graph and M <= 256      # launch bound when driven from Python up to a few hundred tokens
         for i in range(max(warmup, n_copies) if not use_graph else n_copies):
             step(i, xs_, bufs)
         torch.cuda.synchronize()
@@ -449,8 +449,9 @@ def main():
     # ---- extra legs ------------------------------------------------------------------------
     if not args.no_extras:
         sweep = []
-        for M in ([4, 8, 16] if decode_like else [512]):
-            sweep.append(leg(M, max(20, args.steps // 4), 5 if decode_like else 40, 50 if decode_like else 30))
+        for M in ([4, 8, 16, 64, 256] if decode_like else [512]):
+            small = M <= 16
+            sweep.append(leg(M, max(20, args.steps // 4) if small else 40, 5 if small else 40, 50 if small else 30))
         other = leg(2048 if decode_like else 1, 40 if decode_like else 100, 40 if decode_like else 3, 30)
         for extra in sweep + [other]:
             del extra["launches"]

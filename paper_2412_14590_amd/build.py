@@ -49,6 +49,48 @@ def _check_no_scratch(src: str, compile_log: str) -> None:
         raise RuntimeError(f"no resource-usage remark for the hand-issued-load kernels of {src}")
 
 
+def _vregs(text: str) -> set:
+    out = set()
+    for a, b in re.findall(r"\bv\[(\d+):(\d+)\]", text):
+        out |= set(range(int(a), int(b) + 1))
+    out |= {int(a) for a in re.findall(r"\bv(\d+)\b", text)}
+    return out
+
+
+def check_hand_issued_loads(asm_text: str, name: str) -> None:
+    """Scan the gfx950 assembly of a source with hand-issued loads: inside a basic block, between a
+    load written in inline asm and the next inline-asm `s_waitcnt vmcnt`, no instruction of the
+    compiler's may read or write the load's destination registers - the data is not there yet.
+    (This is what happens when a hand-loaded variable is reinterpreted through memory: the compiler
+    keeps it in pieces, splits the register right after the load and reassembles it for the wait.)"""
+    pending, in_asm, bad = {}, False, []
+    for i, line in enumerate(asm_text.split("\n"), 1):
+        t = line.strip()
+        if t.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if t.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        if not t or t.startswith(";"):
+            continue
+        if t.startswith(".") or t.endswith(":") or t.startswith(("s_cbranch", "s_branch", "s_endpgm", "s_setpc")):
+            pending = {}                      # basic block boundary: only straight-line code is judged
+            continue
+        if in_asm:
+            if t.startswith("global_load_") and "_lds_" not in t:
+                for r in _vregs(t.split(",")[0]):
+                    pending[r] = i
+            elif t.startswith("s_waitcnt vmcnt"):
+                pending = {}
+            continue
+        hit = _vregs(t) & set(pending)
+        if hit:
+            bad.append(f"{name}.s:{i}: `{t[:70]}` touches v{sorted(hit)}, hand-loaded at line {pending[min(hit)]}")
+    if bad:
+        raise RuntimeError("registers of hand-issued loads are used before their wait:\n  " + "\n  ".join(bad[:10]))
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Objects are cached per source
     by modification time unless force is set."""
@@ -82,6 +124,19 @@ def build(force: bool = True, verbose: bool = False) -> str:
             print(f"--- {src}\n{out}")
     if failed:
         raise RuntimeError("hipcc failed")
+    # second safety net for the sources with hand-issued loads: their device assembly is scanned
+    asm_procs = []
+    for src in NO_SPILL:
+        a = os.path.join(objdir, src.replace(".hip", ".s"))
+        o = os.path.join(objdir, src.replace(".hip", ".o"))
+        if force or not os.path.exists(a) or os.path.getmtime(a) < os.path.getmtime(o):
+            cmd = [_hipcc(), *FLAGS, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", a]
+            asm_procs.append((src, a, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for src, a, pr in asm_procs:
+        out, _ = pr.communicate()
+        if pr.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed for {src}:\n{out}")
+        check_hand_issued_loads(open(a).read(), src)
     subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     # the ceiling probes of the benchmark: a separate small library
     r = subprocess.run([_hipcc(), *FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, "probe.hip")],

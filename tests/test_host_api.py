@@ -129,3 +129,27 @@ def test_product_path_does_not_import_the_oracle():
     for f in ("binding.py", "synth.py", "__init__.py", "build.py"):
         src = open(os.path.join(ROOT, "paper_2412_14590_amd", f)).read()
         assert "oracle" not in src.replace("oracle-side", ""), f
+
+
+def test_build_scan_flags_a_register_used_between_its_hand_issued_load_and_the_wait():
+    from paper_2412_14590_amd import build
+    ok = """
+	;;#ASMSTART
+	global_load_dwordx2 v[104:105], v119, s[98:99]
+	;;#ASMEND
+	v_add_u32_e32 v1, v2, v3
+	;;#ASMSTART
+	s_waitcnt vmcnt(6)
+	;;#ASMEND
+	v_lshrrev_b32_e32 v128, 16, v104
+"""
+    build.check_hand_issued_loads(ok, "ok")
+    bad = ok.replace("v_add_u32_e32 v1, v2, v3", "v_lshrrev_b32_e32 v128, 16, v104")
+    with pytest.raises(RuntimeError):
+        build.check_hand_issued_loads(bad, "bad")
+    # a branch ends the judged region (the two arms of a conditional load are not one sequence),
+    # and a direct-to-LDS load has no destination register
+    branchy = ok.replace("v_add_u32_e32 v1, v2, v3", "s_branch .LBB1_2\n.LBB1_1:\n\tv_mov_b32_e32 v104, 0")
+    build.check_hand_issued_loads(branchy, "branchy")
+    lds = ok.replace("global_load_dwordx2 v[104:105], v119, s[98:99]", "global_load_lds_dwordx4 v104, s[98:99]")
+    build.check_hand_issued_loads(lds.replace("v_add_u32_e32 v1, v2, v3", "v_mov_b32_e32 v104, 0"), "lds")
