@@ -231,6 +231,16 @@ int mixllm_select_salient(const float *salience, const int64_t *layer_offsets, i
                           size_t workspace_bytes, void *stream);
 
 /*
+ * Test hook (host only, launches nothing): how a kernel of the given path would split the layer
+ * of `d` over its blocks.  path = MIXLLM_PATH_DECODE_SPLIT: plan[0..3] = blocks of the 8-bit part,
+ * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS;
+ * path = MIXLLM_PATH_MID: plan[0..4] = blocks of the 8-bit part, of the 4-bit part, quarter tiles
+ * per virtual tile of the 8-bit and of the 4-bit part, bytes of LDS.  plan must hold 8 ints.
+ * Returns EUNSUPPORTED when the path does not cover the shape, EINVAL for other paths.
+ */
+int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan);
+
+/*
  * Test hook: the exact int32 partial sum of every (token, channel, group), produced by the
  * integer pipeline of the chosen path (same loads, unpacking and MFMA sequence as the
  * linear), written in ORIGINAL channel order:  P int32 [M][N][K/128].

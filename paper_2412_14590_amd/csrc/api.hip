@@ -361,6 +361,21 @@ int mixllm_select_salient(const float *salience, const int64_t *layer_offsets, i
                                                     (hipStream_t)stream));
 }
 
+int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan)
+{
+    if (int rc = check_desc(d)) return rc;
+    if (!plan) return MIXLLM_EINVAL;
+    LinearParams p = make_params(*d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    int out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    bool ok;
+    if (path == MIXLLM_PATH_DECODE_SPLIT) ok = decode_split_plan(p, out);
+    else if (path == MIXLLM_PATH_MID) ok = mid_plan(p, out);
+    else return MIXLLM_EINVAL;
+    if (!ok) return MIXLLM_EUNSUPPORTED;
+    for (int i = 0; i < 8; ++i) plan[i] = out[i];
+    return MIXLLM_OK;
+}
+
 int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const void *packed_w4,
                                 const void *packed_w8, const void *zeros4, const int32_t *feature_perm,
                                 int32_t *P, int path, void *stream)

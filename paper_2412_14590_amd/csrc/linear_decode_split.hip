@@ -521,6 +521,19 @@ bool decode_split_covers(const LinearParams &p)
     return make_plan(p, pl);
 }
 
+// the launch plan as four integers (blocks of the 8-bit part, of the 4-bit part, virtual tiles an
+// LDS cell area covers, bytes of LDS), for the host-side test of the work split
+bool decode_split_plan(const LinearParams &p, int out[4])
+{
+    Plan pl;
+    if (!make_plan(p, pl)) return false;
+    out[0] = pl.nblk8;
+    out[1] = pl.nblk4;
+    out[2] = pl.tcap;
+    out[3] = (int)pl.lds_bytes;
+    return true;
+}
+
 int launch_linear_decode_split(const LinearParams &p, hipStream_t st)
 {
     Plan pl;

@@ -359,16 +359,39 @@ bool mid_covers(const LinearParams &p)
     return p.ntiles8 + p.ntiles4 > 0;
 }
 
-int launch_linear_mid(const LinearParams &p, hipStream_t st)
+static void mid_args(const LinearParams &p, MidArgs &a, size_t &lds_bytes)
 {
-    if (!mid_covers(p)) return (int)hipErrorInvalidValue;
-    MidArgs a;
     a.nblk8 = a.nblk4 = 0;
     split_blocks(4 * p.ntiles8, 4 * p.ntiles4, cu_count(), a.nblk8, a.nblk4);
     a.qv8 = a.nblk8 ? pick_qv(ceil_div(4 * p.ntiles8, a.nblk8)) : 4;
     a.qv4 = a.nblk4 ? pick_qv(ceil_div(4 * p.ntiles4, a.nblk4)) : 4;
     const int mt = token_tiles(p.M);
-    const size_t lds_bytes = (size_t)stage_buffers(mt) * mt * 8 * 1024;
+    lds_bytes = (size_t)stage_buffers(mt) * mt * 8 * 1024;
+}
+
+// the launch plan as five integers (blocks of the 8-bit part, of the 4-bit part, quarter tiles per
+// virtual tile of either part, bytes of LDS), for the host-side test of the work split
+bool mid_plan(const LinearParams &p, int out[5])
+{
+    if (!mid_covers(p)) return false;
+    MidArgs a;
+    size_t lds_bytes;
+    mid_args(p, a, lds_bytes);
+    out[0] = a.nblk8;
+    out[1] = a.nblk4;
+    out[2] = a.qv8;
+    out[3] = a.qv4;
+    out[4] = (int)lds_bytes;
+    return true;
+}
+
+int launch_linear_mid(const LinearParams &p, hipStream_t st)
+{
+    if (!mid_covers(p)) return (int)hipErrorInvalidValue;
+    MidArgs a;
+    size_t lds_bytes;
+    mid_args(p, a, lds_bytes);
+    const int mt = token_tiles(p.M);
     dim3 grid(a.nblk8 + a.nblk4), block(NT);
     auto go = [&](auto kernel) {
         if (lds_bytes > 48 * 1024)

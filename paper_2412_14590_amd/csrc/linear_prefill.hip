@@ -574,7 +574,7 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
     const int nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN, nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
     const int per4 = (nbm * nb4 + 7) / 8, per8 = (nbm * nb8 + 7) / 8;
     dim3 grid((per4 + per8) * 8), block(C::THREADS);
-    const int band = p.tune >= 2 ? min(p.tune, nbm) : min(4, nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
+    const int band = min(4, nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
     if (p.P)
         return launch_variant<C>(linear_prefill_kernel<C, MINW, true, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     if (p.act_per_token && p.w8_per_channel)
@@ -592,8 +592,8 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
     if ((size_t)p.M * (size_t)p.K >= lim || (size_t)p.ntiles4 * TILE_N * (size_t)p.K / 2 >= lim ||
         (size_t)p.ntiles8 * TILE_N * (size_t)p.K >= lim)
         return (int)hipErrorInvalidValue;
-    if (p.tune == 1) return launch_shape<Shape<1, 8, 4>, 2>(p, st);   // 128 x 256, 8 waves
-    return launch_shape<Shape<1, 4, 4>, 2>(p, st);   // 128 x 128, 4 waves, wave tile 128 x 32
+    // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower)
+    return launch_shape<Shape<1, 4, 4>, 2>(p, st);
 }
 
 }  // namespace mixllm

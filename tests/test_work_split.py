@@ -1,0 +1,121 @@
+"""Host-side check of how the weight-streaming kernels split a layer over blocks and waves.
+
+The library reports its launch plan through mixllm_debug_work_split (no GPU needed); the lane ->
+(tile, channel) formulas of the kernels are restated here in plain Python, and for a range of
+shapes every channel row of both precisions must be owned by exactly one valid lane, every tile
+index a lane addresses must exist (clamped lanes included), and a block's LDS cell area must
+cover its virtual tiles.  A mismatch between the host plan and the device formulas would
+otherwise only show as a memory fault on the GPU."""
+import ctypes as C
+
+import pytest
+
+import paper_2412_14590_amd as mx
+from paper_2412_14590_amd import binding
+
+NW = 8
+
+
+def plan(path, M, K, N, n8):
+    out = (C.c_int32 * 8)()
+    d = binding._desc(M, K, N, n8)
+    rc = mx.lib().mixllm_debug_work_split(C.byref(d), path, C.cast(out, C.c_void_p))
+    return rc, list(out)
+
+
+def tiles(N, n8):
+    return (n8 + 15) // 16, (N - n8 + 15) // 16
+
+
+def check_decode_split_part(ntiles, nblk, tcap):
+    """linear_decode_split.hip: whole tiles round robin, the rest in quarter tiles."""
+    if ntiles == 0:
+        assert nblk == 0
+        return
+    assert 1 <= nblk <= 4 * ntiles
+    rounds = ntiles // nblk
+    left_base = 4 * rounds * nblk
+    left = 4 * ntiles - left_base
+    seen = set()
+    for b in range(nblk):
+        L_lo, L_hi = left * b // nblk, left * (b + 1) // nblk
+        assert L_hi - L_lo <= 4
+        nvt = rounds + (1 if L_hi > L_lo else 0)
+        assert 1 <= nvt <= tcap
+        for vt in range(nvt):
+            full = vt < rounds
+            u0 = 4 * (b + nblk * vt) if full else left_base + L_lo
+            cnt = 4 if full else L_hi - L_lo
+            base_tile = u0 >> 2
+            for c in range(16):
+                uc = u0 + min(c >> 2, cnt - 1)
+                row = (uc >> 2) * 16 + 4 * (uc & 3) + (c & 3)
+                rel = row - base_tile * 16
+                assert 0 <= rel < 32 and (uc >> 2) < ntiles and base_tile + (rel >> 4) < ntiles
+                if (c >> 2) < cnt:
+                    assert row not in seen
+                    seen.add(row)
+    assert len(seen) == 16 * ntiles
+
+
+def check_mid_part(ntiles, nblk, qv):
+    """linear_mid.hip: contiguous shares of quarter tiles, qv quarters per virtual tile."""
+    if ntiles == 0:
+        assert nblk == 0
+        return
+    assert 1 <= nblk <= 4 * ntiles and qv in (1, 2, 4)
+    nunits = 4 * ntiles
+    seen = set()
+    for b in range(nblk):
+        Q_lo, Q_hi = nunits * b // nblk, nunits * (b + 1) // nblk
+        nvt = (Q_hi - Q_lo + qv - 1) // qv
+        assert nvt >= 1
+        for vt_raw in range((nvt + NW - 1) // NW * NW):        # idle waves of the last round clamp to the last tile
+            has = vt_raw < nvt
+            u0 = Q_lo + qv * min(vt_raw, nvt - 1)
+            cnt = min(qv, Q_hi - u0)
+            assert cnt >= 1
+            base_tile = u0 >> 2
+            for c in range(16):
+                uc = u0 + min(c >> 2, cnt - 1)
+                row = (uc >> 2) * 16 + 4 * (uc & 3) + (c & 3)
+                rel = row - base_tile * 16
+                assert 0 <= rel < 32 and (uc >> 2) < ntiles and base_tile + (rel >> 4) < ntiles
+                if has and (c >> 2) < cnt:
+                    assert row not in seen
+                    seen.add(row)
+    assert len(seen) == 16 * ntiles
+
+
+SHAPES = [(4096, 4096, 410), (4096, 6144, 614), (4096, 28672, 2867), (14336, 4096, 410), (8192, 10240, 1024),
+          (8192, 57344, 5734), (256, 7, 2), (384, 70, 70), (1024, 530, 0), (640, 50, 5), (128, 16, 16), (512, 4097, 1),
+          (4096, 14336, 10178), (2048, 2070, 207), (128, 33, 3)]
+
+
+@pytest.mark.parametrize("K,N,n8", SHAPES)
+def test_decode_split_plan_covers_every_channel_once(K, N, n8):
+    t8, t4 = tiles(N, n8)
+    for M in (1, 4, 16):
+        rc, p = plan(mx.PATH_DECODE_SPLIT, M, K, N, n8)
+        if M * K > 65536:
+            assert rc == -2            # the activations do not fit the LDS stage: not covered, not an error path
+            continue
+        assert rc == 0, (M, K, N, n8)
+        nblk8, nblk4, tcap, lds = p[:4]
+        assert lds <= 160 * 1024
+        check_decode_split_part(t8, nblk8, tcap)
+        check_decode_split_part(t4, nblk4, tcap)
+
+
+@pytest.mark.parametrize("K,N,n8", SHAPES)
+def test_mid_plan_covers_every_channel_once(K, N, n8):
+    t8, t4 = tiles(N, n8)
+    for M in (17, 33, 64):
+        rc, p = plan(mx.PATH_MID, M, K, N, n8)
+        assert rc == 0, (M, K, N, n8)
+        nblk8, nblk4, qv8, qv4, lds = p[:5]
+        assert lds <= 160 * 1024
+        check_mid_part(t8, nblk8, qv8)
+        check_mid_part(t4, nblk4, qv4)
+    assert plan(mx.PATH_MID, 65, K, N, n8)[0] == -2
+    assert plan(mx.PATH_PREFILL, 64, K, N, n8)[0] == -1
