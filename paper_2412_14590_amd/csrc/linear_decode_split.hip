@@ -109,7 +109,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     constexpr int NLW = PART8 ? 8 : 4;
     constexpr int NLM = PART8 ? (DUMP ? 0 : 1) : (DUMP ? 1 : 2);
     constexpr int NL = NLW + NLM;               // loads per chunk
-    constexpr int MAXV = FUSED ? 4 : (NR == 1 ? 16 : 8);   // staging loads per thread (up to 4 tokens: 128 KB of activations)
+    constexpr int MAXV = FUSED ? 4 : 16;        // staging loads per thread (up to 128 KB of activations)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, ks = lane >> 4;
@@ -442,13 +442,16 @@ bool compute_plan(const LinearParams &p, Plan &o)
     if (p.M < 1 || p.M > 16 || p.ng < 1) return false;
     const bool fused = p.x != nullptr;
     if (fused && (p.M != 1 || !p.act_per_token || p.P || p.K > NT * 8 * 4)) return false;
-    if (!fused && (size_t)p.M * p.K > (size_t)NT * 16 * (p.M <= 4 ? 16 : 8)) return false;
+    if (!fused && (size_t)p.M * p.K > (size_t)NT * 16 * 16) return false;
     o.nr = p.M <= 4 ? 1 : 4;
     const int nquads = (p.ng + 3) / 4;
     const long long units8 = 4ll * p.ntiles8, units4 = 4ll * p.ntiles4;
     if (units8 + units4 == 0 || std::max(units8, units4) * MAX_BLOCKS >= (1ll << 31)) return false;
     const size_t fixed = 64 + (p.act_per_token ? 0 : ((size_t)p.M * p.ng + 3) / 4 * 16) + (size_t)p.M * (p.K + A_PAD);
     for (int nb = cu_count(); nb <= MAX_BLOCKS; nb *= 2) {
+        // every block stages the whole activation matrix: with more than 64 KB of it, more than one
+        // block per CU costs more than it gains (the kernel for a few dozen tokens takes those shapes)
+        if (nb > cu_count() && fixed > 64 * 1024 + 4096) return false;
         int nblk8 = 0, nblk4 = 0;
         split_blocks((int)units8, (int)units4, nb, nblk8, nblk4);
         int share = 1;   // most quarter tiles in one block

@@ -25,7 +25,7 @@ def say(*a):
 
 def split_variant_covers(M, K):
     """The evenly split decode variant stages the whole int8 activation matrix in LDS."""
-    return M <= 16 and M * K <= (131072 if M <= 4 else 65536)
+    return M <= 16 and M * K <= 131072
 
 
 def skip_unless_covered(path, M, K):
