@@ -231,6 +231,15 @@ int mixllm_select_salient(const float *salience, const int64_t *layer_offsets, i
                           size_t workspace_bytes, void *stream);
 
 /*
+ * Test hook: the quantizer kernels round v / s (v, s fp16 values) with a reciprocal, a product and
+ * one residual correction instead of a division.  This call compares, on the GPU, the rounded
+ * result with that of the IEEE division for every finite fp16 v and every positive finite fp16 s
+ * (2.0e9 pairs) and adds the number of differences to *mismatches (device, uint64, zeroed by the
+ * caller).  Errors: EINVAL, EHIP.
+ */
+int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream);
+
+/*
  * Test hook (host only, launches nothing): how a kernel of the given path would split the layer
  * of `d` over its blocks.  path = MIXLLM_PATH_DECODE_SPLIT: plan[0..3] = blocks of the 8-bit part,
  * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS;

@@ -66,6 +66,8 @@ def lib():
         L.mixllm_select_salient_workspace.argtypes = [C.c_int32]
         L.mixllm_select_salient_workspace.restype = C.c_size_t
         L.mixllm_select_salient.argtypes = [_VP, _VP, C.c_int32, C.c_int64, _VP, _VP, _VP, C.c_size_t, _VP]
+        L.mixllm_debug_check_fast_division.argtypes = [_VP, _VP]
+        L.mixllm_debug_check_fast_division.restype = C.c_int
         L.mixllm_debug_work_split.argtypes = [C.POINTER(_Desc), C.c_int, _VP]
         L.mixllm_debug_work_split.restype = C.c_int
         L.mixllm_channel_salience.restype = C.c_int

@@ -361,6 +361,12 @@ int mixllm_select_salient(const float *salience, const int64_t *layer_offsets, i
                                                     (hipStream_t)stream));
 }
 
+int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream)
+{
+    if (!mismatches || ((uintptr_t)mismatches & 7u)) return MIXLLM_EINVAL;
+    return hip_status(launch_check_fast_division((unsigned long long *)mismatches, (hipStream_t)stream));
+}
+
 int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan)
 {
     if (int rc = check_desc(d)) return rc;

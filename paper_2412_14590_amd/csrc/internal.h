@@ -91,8 +91,32 @@ static inline __device__ half_t store_scale(float s32)
     if ((float)s16 == 0.0f) s16 = (half_t)1.0f;
     return s16;
 }
-// one int8 code: IEEE division, ties to even, clamp to [-127, 127]; returned in the low byte
-static inline __device__ uint32_t quant_code(half_t v, float s)
+// The quantizers need round(v / s) with v and s both fp16-valued and the true (IEEE) quotient
+// rounded half to even.  A full fp32 division is a dozen vector instructions; the quantizers are
+// bound by them.  quotient() takes the reciprocal r = rcp(s) (one instruction per scale, 1 ulp),
+// the product v r and one residual correction.  Its result is not always the correctly rounded
+// quotient, but rint() of it equals rint() of the correctly rounded quotient for EVERY pair of
+// finite fp16 values: a quotient of two 11-bit significands that is not itself a multiple of 1/2 is
+// at least 2^-15 away from one, far more than the error left after the correction, and an exact
+// multiple of 1/2 comes out exactly.  mixllm_debug_check_fast_division compares the two for all
+// 2.0e9 pairs on the GPU (no mismatch); the parity tests compare the codes with the oracle's,
+// which divides.
+static inline __device__ float recip(float s) { return __builtin_amdgcn_rcpf(s); }
+static inline __device__ float quotient(float v, float s, float r)
+{
+    const float t0 = v * r;
+    const float e = __builtin_fmaf(-t0, s, v);
+    return __builtin_fmaf(e, r, t0);
+}
+// one int8 code: v / s rounded half to even, clamped to [-127, 127]; returned in the low byte
+static inline __device__ uint32_t quant_code(half_t v, float s, float r)
+{
+    float t = __builtin_rintf(quotient((float)v, s, r));
+    t = fminf(fmaxf(t, -127.0f), 127.0f);
+    return (uint32_t)(int)t & 0xffu;
+}
+// the same with the IEEE division (the reference of the exhaustive check)
+static inline __device__ uint32_t quant_code_ieee(half_t v, float s)
 {
     float t = __builtin_rintf((float)v / s);
     t = fminf(fmaxf(t, -127.0f), 127.0f);
@@ -102,6 +126,7 @@ static inline __device__ uint32_t quant_code(half_t v, float s)
 // ---- launchers (defined one per .hip file); return a hipError_t as int ----
 int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq, void *xs,
                                 hipStream_t st);
+int launch_check_fast_division(unsigned long long *mismatches, hipStream_t st);
 int launch_quantize_weights(const mixllm_desc &d, const void *W, void *w8, void *w4, void *s8,
                             void *s4, void *z4, const int32_t *perm, hipStream_t st);
 int launch_pack_weights(const mixllm_desc &d, const int8_t *q8, const void *s8c, const uint8_t *q4,

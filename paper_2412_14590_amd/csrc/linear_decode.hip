@@ -382,11 +382,12 @@ static __device__ inline void decode_resident(const LinearParams &p, int tile_be
                     sc = (float)store_scale(amax / 127.0f);
                     if ((lane & 15) == 0) qs->scale[wave][r][lane >> 4] = sc;
                 }
+                const float rc = recip(sc);
                 uint32_t w0 = 0, w1 = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    w0 |= quant_code(xv[i], sc) << (8 * i);
-                    w1 |= quant_code(xv[4 + i], sc) << (8 * i);
+                    w0 |= quant_code(xv[i], sc, rc) << (8 * i);
+                    w1 |= quant_code(xv[4 + i], sc, rc) << (8 * i);
                 }
                 *(uint2 *)&qs->code[wave][r][8 * lane] = make_uint2(w0, w1);
             }

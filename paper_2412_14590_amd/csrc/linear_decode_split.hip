@@ -242,6 +242,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
 #pragma unroll
         for (int w = 0; w < NW; ++w) rowmax = fmaxf(rowmax, wmax[w]);
         const float sc = (float)store_scale(rowmax / 127.0f);
+        const float rc = recip(sc);
 #pragma unroll
         for (int j = 0; j < MAXV; ++j) {
             const int i = tid + NT * j;
@@ -250,8 +251,8 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
                 uint32_t w0 = 0, w1 = 0;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    w0 |= quant_code(hv[e], sc) << (8 * e);
-                    w1 |= quant_code(hv[4 + e], sc) << (8 * e);
+                    w0 |= quant_code(hv[e], sc, rc) << (8 * e);
+                    w1 |= quant_code(hv[4 + e], sc, rc) << (8 * e);
                 }
                 *(uint2 *)(lds_x + i * 8) = make_uint2(w0, w1);
             }

@@ -16,12 +16,31 @@ static __device__ inline float wave_max(float v)
 
 static __device__ inline uint2 quant8(const h8 &v, float s)
 {
+    const float r = recip(s);
     uint32_t w[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        w[i >> 2] |= quant_code(v[i], s) << (8 * (i & 3));
+        w[i >> 2] |= quant_code(v[i], s, r) << (8 * (i & 3));
     }
     return make_uint2(w[0], w[1]);
+}
+
+// Exhaustive check of quotient(): for every positive finite fp16 scale (one block each) and every
+// finite fp16 value the int8 code from quotient() against the code from the IEEE division.
+__global__ __launch_bounds__(256) void check_fast_division_kernel(unsigned long long *mismatches)
+{
+    const uint16_t sb = (uint16_t)(blockIdx.x + 1);   // 0x0001 .. 0x7BFF
+    const float s = (float)__builtin_bit_cast(half_t, sb);
+    const float r = recip(s);
+    unsigned long long bad = 0;
+    for (int xb = threadIdx.x; xb < 65536; xb += 256) {
+        if ((xb & 0x7C00) == 0x7C00) continue;   // infinities and NaNs
+        const half_t x = __builtin_bit_cast(half_t, (uint16_t)xb);
+        bad += quant_code(x, s, r) != quant_code_ieee(x, s);
+        // the 4-bit weight quantizer rounds the same quotient without the int8 clamp
+        bad += __builtin_rintf(quotient((float)x, s, r)) != __builtin_rintf((float)x / s);
+    }
+    if (bad) atomicAdd(mismatches, bad);
 }
 
 // One block per token, the row held in registers between the absmax pass and the quantizing
@@ -106,6 +125,12 @@ __global__ __launch_bounds__(256) void act_quant_per_group(const half_t *__restr
     half_t s16 = store_scale(amax / 127.0f);
     if ((threadIdx.x & 15) == 0) xs[(size_t)m * ng + g] = s16;
     *(uint2 *)(xq + off) = quant8(d, (float)s16);
+}
+
+int launch_check_fast_division(unsigned long long *mismatches, hipStream_t st)
+{
+    hipLaunchKernelGGL(check_fast_division_kernel, dim3(0x7BFF), dim3(256), 0, st, mismatches);
+    return (int)hipGetLastError();
 }
 
 int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq, void *xs,

@@ -73,10 +73,11 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                     s = (float)s16;
                 }
                 uint32_t w[4] = {0, 0, 0, 0};
+                const float rs = recip(s);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     float v = (i < 8) ? (float)a[i] : (float)b[i - 8];
-                    float t = fminf(fmaxf(__builtin_rintf(v / s), -127.0f), 127.0f);
+                    float t = fminf(fmaxf(__builtin_rintf(quotient(v, s, rs)), -127.0f), 127.0f);
                     w[i >> 2] |= ((uint32_t)(int)t & 0xffu) << (8 * (i & 3));
                 }
                 out = make_uint4(w[0], w[1], w[2], w[3]);
@@ -111,11 +112,12 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(
                 }
                 s16 = store_scale((mx - mn) / 15.0f);
                 sc = (float)s16;
-                zf = fminf(fmaxf(__builtin_rintf(-mn / sc), 0.0f), 15.0f);
+                const float rsc = recip(sc);
+                zf = fminf(fmaxf(__builtin_rintf(quotient(-mn, sc, rsc)), 0.0f), 15.0f);
                 uint32_t code[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    float t = __builtin_rintf((float)v[i] / sc) + zf;
+                    float t = __builtin_rintf(quotient((float)v[i], sc, rsc)) + zf;
                     code[i] = (uint32_t)(int)fminf(fmaxf(t, 0.0f), 15.0f);
                 }
 #pragma unroll

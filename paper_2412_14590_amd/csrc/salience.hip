@@ -42,11 +42,12 @@ __global__ __launch_bounds__(256) void channel_salience_kernel(const half_t *__r
             mx = fmaxf(mx, __shfl_xor(mx, o, 16));
         }
         const float sc = (float)store_scale((mx - mn) / 15.0f);
-        const float zf = fminf(fmaxf(__builtin_rintf(-mn / sc), 0.0f), 15.0f);
+        const float rsc = recip(sc);
+        const float zf = fminf(fmaxf(__builtin_rintf(quotient(-mn, sc, rsc)), 0.0f), 15.0f);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const float wf = (float)w[i];
-            const float code = fminf(fmaxf(__builtin_rintf(wf / sc) + zf, 0.0f), 15.0f);
+            const float code = fminf(fmaxf(__builtin_rintf(quotient(wf, sc, rsc)) + zf, 0.0f), 15.0f);
             const float delta = (code - zf) * sc - wf;   // quantize(W) - W
             acc = __builtin_fmaf((float)g[i], delta, acc);
         }

@@ -55,6 +55,15 @@ def test_activation_quantizer_bit_exact(M, K, grouped):
     assert np.array_equal(xq.cpu().numpy(), xq_ref)
 
 
+def test_quantizer_division_shortcut_is_exact_for_every_fp16_pair():
+    # the kernels round v / s through a reciprocal and one correction step; on the GPU, against the
+    # IEEE division, for all 63488 finite fp16 values times all 31743 positive finite fp16 scales
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    rc = mx.lib().mixllm_debug_check_fast_division(bad.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert rc == 0 and int(bad.item()) == 0
+
+
 def test_activation_quantizer_empty_batch():
     x = torch.empty((0, 256), dtype=torch.float16, device="cuda")
     xq, xs = mx.quantize_activations(x)
