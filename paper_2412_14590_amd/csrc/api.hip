@@ -70,9 +70,7 @@ LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xsc
     p.s8 = (const half_t *)s8;
     p.z4 = (const uint8_t *)z4;
     p.perm = perm;
-    // MIXLLM_TUNE selects an alternative launch shape inside a path (tuning experiments only)
-    static const int tune = [] { const char *e = getenv("MIXLLM_TUNE"); return e ? atoi(e) : 0; }();
-    p.tune = tune;
+    p.variant = DECODE_ANY;
     return p;
 }
 
@@ -126,8 +124,8 @@ int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t 
     case MIXLLM_PATH_DECODE_RESIDENT:
     case MIXLLM_PATH_DECODE_SPLIT: {
         if (d.M > 16) return MIXLLM_EUNSUPPORTED;
-        LinearParams q = p;   // the variants are what the tuning override selects
-        q.tune = path == MIXLLM_PATH_DECODE_STREAM ? 999 : path == MIXLLM_PATH_DECODE_RESIDENT ? 1000 : 3000;
+        LinearParams q = p;
+        q.variant = path == MIXLLM_PATH_DECODE_STREAM ? DECODE_STREAM : path == MIXLLM_PATH_DECODE_RESIDENT ? DECODE_RESIDENT : DECODE_SPLIT;
         if (path == MIXLLM_PATH_DECODE_SPLIT && !decode_split_covers(q)) return MIXLLM_EUNSUPPORTED;
         return hip_status(launch_linear_decode(q, st));
     }
@@ -313,10 +311,8 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
     p.y = (half_t *)y;
     // One kernel when the decode path can quantize inside the linear and it pays: measured on the
     // Llama-shaped layers the built-in quantizer wins for a single token, ties at two and loses
-    // from three on (its work is repeated by every block).  MIXLLM_TUNE=2000 takes it whenever
-    // it is possible (tests of the M = 2..4 code).
-    if (decode_can_fuse_quantizer(p) && (d->M == 1 || p.tune == 2000)) {
-        if (p.tune == 2000) p.tune = 0;
+    // from three on (its work is repeated by every block), so it is built for one token only.
+    if (d->M == 1 && decode_can_fuse_quantizer(p)) {
         p.x = (const half_t *)x;
         return hip_status(launch_linear_decode(p, (hipStream_t)stream));
     }

@@ -20,6 +20,9 @@ constexpr int TILE_N = 16;        // rows of one packed weight tile
 static inline __host__ __device__ int round_up(int a, int b) { return (a + b - 1) / b * b; }
 
 // Everything a linear / partials kernel needs, by value.
+// decode variants a caller can name through the path argument of the linear entry points
+enum DecodeVariant { DECODE_ANY = 0, DECODE_STREAM, DECODE_RESIDENT, DECODE_SPLIT };
+
 struct LinearParams {
     int M, K, N, n8, n4;
     int ng;         // K / 128
@@ -28,7 +31,7 @@ struct LinearParams {
     int ntiles4;    // n4p / 16
     int act_per_token;   // 1: xscale [M], 0: xscale [M][ng]
     int w8_per_channel;  // 1: scales8 [n8p], 0: scales8 [n8p][ngp]
-    int tune;            // launch-shape override for experiments (0 = library default)
+    int variant;         // decode variant requested by the caller's path argument (DECODE_ANY = library's choice)
     const half_t *x;   // fp16 activations [M][K]: set only by the fused quantize + linear entry point
     const int8_t *xq;
     const half_t *xscale;

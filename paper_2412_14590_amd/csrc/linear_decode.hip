@@ -310,10 +310,11 @@ struct ResItem {   // one (slab, tile) item of one wave: 4 groups of one tile
 // first weight loads are in flight (Sec. 2 formula, z = 0; the same arithmetic as the stand-alone
 // quantizer, so the codes are identical): wave w quantizes its own 512 k of every token row
 // (the row maxima of the waves meet in LDS), leaves the codes in LDS and picks its A fragments
-// up from there.  The work per block is that of the whole stand-alone quantizer, so this only
-// pays for very few tokens (M <= 4), and it requires a single slab (K <= WPB * 512).
+// up from there.  The work per block is that of the whole stand-alone quantizer: measured, it
+// wins for one token, ties at two and loses from three on, so it is built for one token; and it
+// requires a single slab (K <= WPB * 512).
 typedef half_t h8v __attribute__((ext_vector_type(8)));
-constexpr int FUSED_MAX_M = 4;
+constexpr int FUSED_MAX_M = 1;
 
 template <int WPB>
 struct QuantScratch {
@@ -583,10 +584,16 @@ static int launch_resident(const LinearParams &p, int nblk8, int per8, int nblk4
     dim3 grid(nblk8 + nblk4), block(WPB * 64);
     if (p.P)
         hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, true, true, false>), grid, block, 0, st, p, nblk8, per8, per4);
-    else if (p.x && p.act_per_token)
-        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, true, true>), grid, block, 0, st, p, nblk8, per8, per4);
-    else if (p.x)
-        hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, false, true>), grid, block, 0, st, p, nblk8, per8, per4);
+    else if (p.x) {
+        if constexpr (NR == 1) {   // fp16 activations: one token only (resident_can_fuse)
+            if (p.act_per_token)
+                hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, 1, false, true, true>), grid, block, 0, st, p, nblk8, per8, per4);
+            else
+                hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, 1, false, false, true>), grid, block, 0, st, p, nblk8, per8, per4);
+        } else {
+            return (int)hipErrorInvalidValue;
+        }
+    }
     else if (p.act_per_token)
         hipLaunchKernelGGL((linear_decode_resident_kernel<WPB, NR, false, true, false>), grid, block, 0, st, p, nblk8, per8, per4);
     else
@@ -628,10 +635,10 @@ static bool resident_can_fuse(const LinearParams &p)
 // the two older variants (67 MB of weights, one token: 13.9 us against 16.2; 34 MB with
 // K = 14336: 11.1 against 13.0; 16 tokens: 15.7 against 19.6) and is within 0.3 us of the
 // resident variant on the smallest (8 MB, one token: 6.0 against 5.8; faster from two tokens
-// on).  tune >= 3000 forces it, tune 1..2999 keeps it off (experiments, variant tests).
+// on).  A caller that names another variant gets that one.
 static bool prefer_split(const LinearParams &p)
 {
-    return p.tune == 0 || p.tune >= 3000;
+    return p.variant == DECODE_ANY || p.variant == DECODE_SPLIT;
 }
 
 // fp16 activations (p.x set on the copy that is tested) can be taken by one of the variants
@@ -650,7 +657,7 @@ int launch_linear_decode(const LinearParams &p, hipStream_t st)
     // a few dozen tokens stages the activations per K step and measured 10-25 % faster than the streaming
     // variant on layers of at least two tiles per CU (Llama-3.1-70B shapes, M = 16: 16.7 vs 20.7, 16.1 vs
     // 19.0, 56.9 vs 63.7, 48.1 vs 58.9 us), slower on smaller ones (one tile per CU: 30 vs 20 us).
-    if (p.tune == 0 && !p.x && p.ntiles8 + p.ntiles4 >= 512 && mid_covers(p)) return launch_linear_mid(p, st);
+    if (p.variant == DECODE_ANY && !p.x && p.ntiles8 + p.ntiles4 >= 512 && mid_covers(p)) return launch_linear_mid(p, st);
     if (p.x) {   // fused quantizer
         if (!resident_can_fuse(p)) return (int)hipErrorInvalidValue;
         const int rc = try_launch_resident<8>(p, 1, st);
@@ -658,21 +665,17 @@ int launch_linear_decode(const LinearParams &p, hipStream_t st)
     }
     const int tiles = p.ntiles8 + p.ntiles4;
     // Resident variant where it measured faster on the Llama-shaped layers: K of one slab
-    // (K <= 4096) and either few tiles or a single token.  tune 1..999 forces the streaming
-    // variant, tune >= 1000 the resident one (experiments).
-    const bool resident = p.tune == 0 ? (p.ng <= 32 && (tiles <= 1024 || p.M == 1)) : p.tune >= 1000;
+    // (K <= 4096) and either few tiles or a single token.
+    const bool resident = p.variant == DECODE_STREAM ? false
+                        : p.variant == DECODE_RESIDENT ? true : (p.ng <= 32 && (tiles <= 1024 || p.M == 1));
     if (resident) {
         const int rc = try_launch_resident<8>(p, 1, st);
         if (rc >= 0) return rc;
     }
     const int nquads = (p.ng + 3) / 4;
-    int tpw = (tiles >= 300 && p.M > 4) ? 2 : 1;
+    const int tpw = (tiles >= 300 && p.M > 4) ? 2 : 1;
     int wpb = 1;
     while (wpb < 8 && wpb * 2 <= nquads && tiles * wpb * 2 <= 2048) wpb *= 2;
-    if (p.tune > 0 && p.tune < 900) {   // experiments: tune = 100 * tpw + wpb
-        tpw = p.tune / 100;
-        wpb = p.tune % 100;
-    }
     return tpw == 2 ? launch_wpb<2>(p, wpb, st) : launch_wpb<1>(p, wpb, st);
 }
 
