@@ -309,10 +309,10 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
         return MIXLLM_EINVAL;
     LinearParams p = make_params(*d, nullptr, nullptr, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm);
     p.y = (half_t *)y;
-    // One kernel when the decode path can quantize inside the linear and it pays: measured on the
-    // Llama-shaped layers the built-in quantizer wins for a single token, ties at two and loses
-    // from three on (its work is repeated by every block), so it is built for one token only.
-    if (d->M == 1 && decode_can_fuse_quantizer(p)) {
+    // One kernel when a decode variant can quantize inside the linear: every block then repeats the
+    // quantizer, so the variants only offer it where that measured cheaper than the stand-alone
+    // kernel's launch and round trips (one token; a few tokens of a short row).
+    if (decode_can_fuse_quantizer(p)) {
         p.x = (const half_t *)x;
         return hip_status(launch_linear_decode(p, (hipStream_t)stream));
     }

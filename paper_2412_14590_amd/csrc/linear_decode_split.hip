@@ -45,6 +45,7 @@ namespace {
 constexpr int NW = 8;              // waves per block
 constexpr int NT = NW * 64;
 constexpr int A_PAD = 16;          // bytes added to every staged activation row
+constexpr int LDS_HEADER = 128;    // row maxima of the built-in quantizers in front of the cells
 constexpr int MAX_BLOCKS = 2048;
 constexpr size_t LDS_LIMIT = 156 * 1024;
 
@@ -101,7 +102,9 @@ __device__ inline void await_vec(v4i &a)
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
 }
 
-template <int NR, bool DUMP, bool ACT_PT, bool PART8, bool FUSED>
+// FUSED: 0 = int8 codes and scales come from the stand-alone quantizer; 1 = one token of fp16
+// activations, 2 = several tokens of them (K a multiple of 512), quantized by every block for itself
+template <int NR, bool DUMP, bool ACT_PT, bool PART8, int FUSED>
 __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, uint8_t *smem)
 {
     constexpr int D = 2;   // chunk requests in flight per wave, one of them being consumed (measured on 8 to 67 MB layers: every further slot costs 0.3 to 0.7 us)
@@ -109,7 +112,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     constexpr int NLW = PART8 ? 8 : 4;
     constexpr int NLM = PART8 ? (DUMP ? 0 : 1) : (DUMP ? 1 : 2);
     constexpr int NL = NLW + NLM;               // loads per chunk
-    constexpr int MAXV = FUSED ? 4 : 16;        // staging loads per thread (up to 128 KB of activations)
+    constexpr int MAXV = FUSED ? 4 : 16;   // staging loads per thread (up to 128 KB of int8 codes, or 32 KB of fp16 values)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, ks = lane >> 4;
@@ -139,7 +142,8 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
 
     // ---- LDS ----
     float *wmax = (float *)smem;                                     // [NW] row maxima (built-in quantizer)
-    float *red = (float *)(smem + 64);                               // [tcap][NW][NR][64]
+    uint32_t *tokmax = (uint32_t *)(smem + 64);                      // [16] row maxima as float bits (built-in quantizer, several tokens)
+    float *red = (float *)(smem + LDS_HEADER);                       // [tcap][NW][NR][64]
     float *xsg = red + (size_t)a.tcap * NW * NR * 64;                // [M][ng] group scales of the activations
     int8_t *lds_x = (int8_t *)(xsg + (ACT_PT ? 0 : (p.M * ng + 3) / 4 * 4));
 
@@ -190,7 +194,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
 
     // ---- 1. activations on their way, then the first weight requests ----
     v4i xv[MAXV];
-    const int npiece = FUSED ? p.K / 8 : p.M * (p.K / 16);   // 16-byte pieces of the activation matrix
+    const int npiece = FUSED ? p.M * (p.K / 8) : p.M * (p.K / 16);   // 16-byte pieces of the activation matrix
     const void *xsrc = FUSED ? (const void *)p.x : (const void *)p.xq;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
@@ -218,12 +222,57 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
         for (int r = 0; r < NR; ++r) red[((vt * NW + wave) * NR + r) * 64 + lane] = 0.0f;
     if (!ACT_PT && !DUMP)
         for (int i = tid; i < p.M * ng; i += NT) xsg[i] = (float)p.xscale[i];
+    if (FUSED == 2) {
+        if (tid < 16) tokmax[tid] = 0u;
+        lds_barrier();   // while the activations are still on their way
+    }
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
         if (j * NT < npiece) await_vec<(D - 1) * NL>(xv[j]);
 
     // ---- 2. stage the activations ----
-    if (FUSED) {
+    if (FUSED == 2) {
+        // Several tokens.  K is a multiple of 512, so the 64 pieces of one load of a wave lie in
+        // one token row: the wave reduces their maximum and one lane folds it into the row's
+        // cell (non-negative floats order like their bit patterns).
+        const int per_row = p.K / 8;
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int i0 = wave * 64 + NT * j;   // first piece of the wave's load j
+            if (j * NT < npiece && i0 < npiece) {
+                const h8 hv = __builtin_bit_cast(h8, xv[j]);   // the whole register, after its wait
+                float amax = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf((float)hv[e]));
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+                if (lane == 0) atomicMax(&tokmax[i0 / per_row], __builtin_bit_cast(uint32_t, amax));
+            }
+        }
+        lds_barrier();
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int i0 = wave * 64 + NT * j;
+            if (j * NT < npiece && i0 < npiece) {
+                const int tok = i0 / per_row, pos = i0 - tok * per_row + lane;
+                const float sc = (float)store_scale(__builtin_bit_cast(float, tokmax[tok]) / 127.0f);
+                const float rc = recip(sc);
+                const h8 hv = __builtin_bit_cast(h8, xv[j]);
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    w0 |= quant_code(hv[e], sc, rc) << (8 * e);
+                    w1 |= quant_code(hv[4 + e], sc, rc) << (8 * e);
+                }
+                *(uint2 *)(lds_x + tok * xstride + pos * 8) = make_uint2(w0, w1);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const int m = min(NR == 1 ? ks : 4 * ks + r, p.M - 1);
+            xs_tok[r] = (float)store_scale(__builtin_bit_cast(float, tokmax[m]) / 127.0f);
+        }
+    } else if (FUSED == 1) {
         // one token: row maximum over all threads, then the codes
         float amax = 0.0f;
 #pragma unroll
@@ -385,7 +434,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     }
 }
 
-template <int NR, bool DUMP, bool ACT_PT, bool FUSED>
+template <int NR, bool DUMP, bool ACT_PT, int FUSED>
 __global__ __launch_bounds__(NT) void linear_decode_split_kernel(LinearParams p, SplitArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -442,13 +491,18 @@ bool compute_plan(const LinearParams &p, Plan &o)
 {
     if (p.M < 1 || p.M > 16 || p.ng < 1) return false;
     const bool fused = p.x != nullptr;
-    if (fused && (p.M != 1 || !p.act_per_token || p.P || p.K > NT * 8 * 4)) return false;
+    // fp16 activations: per-token scales only, at most 4 loads per thread (16 Ki values); several
+    // tokens need K = a multiple of 512.  Every block repeats the quantizer: measured on the
+    // Llama-3-8B block, 16 Ki values cost as much as the stand-alone kernel they replace
+    // (52.2 against 52.7 us per step at M = 4), 32 Ki values much more (68.0 against 57.7 at M = 8).
+    if (fused && (!p.act_per_token || p.P || (size_t)p.M * p.K > (size_t)NT * 8 * 4)) return false;
+    if (fused && p.M > 1 && p.K % 512 != 0) return false;
     if (!fused && (size_t)p.M * p.K > (size_t)NT * 16 * 16) return false;
     o.nr = p.M <= 4 ? 1 : 4;
     const int nquads = (p.ng + 3) / 4;
     const long long units8 = 4ll * p.ntiles8, units4 = 4ll * p.ntiles4;
     if (units8 + units4 == 0 || std::max(units8, units4) * MAX_BLOCKS >= (1ll << 31)) return false;
-    const size_t fixed = 64 + (p.act_per_token ? 0 : ((size_t)p.M * p.ng + 3) / 4 * 16) + (size_t)p.M * (p.K + A_PAD);
+    const size_t fixed = LDS_HEADER + (p.act_per_token ? 0 : ((size_t)p.M * p.ng + 3) / 4 * 16) + (size_t)p.M * (p.K + A_PAD);
     for (int nb = cu_count(); nb <= MAX_BLOCKS; nb *= 2) {
         // every block stages the whole activation matrix: with more than 64 KB of it, more than one
         // block per CU costs more than it gains (the kernel for a few dozen tokens takes those shapes)
@@ -511,10 +565,14 @@ int launch_nr(const LinearParams &p, const SplitArgs &a, size_t lds_bytes, hipSt
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, a);
         return (int)hipGetLastError();
     };
-    if (p.P) return go(linear_decode_split_kernel<NR, true, true, false>);
-    if (p.x) return go(linear_decode_split_kernel<NR, false, true, true>);
-    if (p.act_per_token) return go(linear_decode_split_kernel<NR, false, true, false>);
-    return go(linear_decode_split_kernel<NR, false, false, false>);
+    if (p.P) return go(linear_decode_split_kernel<NR, true, true, 0>);
+    if (p.x && p.M > 1) return go(linear_decode_split_kernel<NR, false, true, 2>);
+    if (p.x) {
+        if constexpr (NR == 1) return go(linear_decode_split_kernel<1, false, true, 1>);
+        return (int)hipErrorInvalidValue;
+    }
+    if (p.act_per_token) return go(linear_decode_split_kernel<NR, false, true, 0>);
+    return go(linear_decode_split_kernel<NR, false, false, 0>);
 }
 
 }  // namespace

@@ -230,12 +230,14 @@ def test_auto_dispatch_and_end_to_end_from_fp16():
 @pytest.mark.parametrize("M,K,N,n8", [(1, 4096, 4096, 410), (1, 1024, 100, 9), (4, 640, 50, 0), (7, 384, 40, 40),
                                      (16, 4096, 1024, 102), (3, 128, 33, 3), (2, 2048, 2070, 207), (4, 4096, 600, 60),
                                      (3, 14336, 96, 10), (40, 512, 64, 6), (1, 14336, 272, 27), (1, 8192, 4100, 400),
-                                     (1, 16384, 48, 5)])
+                                     (1, 16384, 48, 5), (8, 2048, 300, 30), (2, 8192, 64, 6), (5, 1024, 100, 10),
+                                     (8, 512, 40, 4), (16, 1024, 530, 53), (3, 4096, 1000, 100)])
 def test_fused_quantizer_and_linear_from_fp16(M, K, N, n8, variant):
     # one call from fp16 activations: for M = 1 the decode kernel quantizes its own activations
     # where a variant can (K <= 4096: resident variant; K <= 16384 with per-token scales: split
-    # variant); the result must equal the oracle (quantizer + linear) and agree with the
-    # two-call GPU path on the same inputs
+    # variant), and so does the split variant for a few tokens of a short row (K a multiple of 512,
+    # M K <= 16384, per-token scales); the result must equal the oracle (quantizer + linear) and
+    # agree with the two-call GPU path on the same inputs
     w8g, ag = (None, None) if variant == "baseline" else (128, 128)
     W, sal, L, x, xq, xs = make_case(M, K, N, n8, seed=31, w8_group=w8g, act_group=ag)
     PL = pack_from_oracle(L)
