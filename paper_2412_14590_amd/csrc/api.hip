@@ -77,6 +77,19 @@ LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xsc
 }  // namespace
 
 namespace mixllm {
+int cu_count()
+{
+    static int n[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (n[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        n[dev] = v;
+    }
+    return n[dev];
+}
+
 int ensure_dynamic_lds(const void *kernel, size_t bytes)
 {
     // (kernel, device) pairs already configured with at least this size; a few dozen instantiations exist

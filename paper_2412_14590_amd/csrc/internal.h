@@ -147,6 +147,8 @@ bool decode_split_plan(const LinearParams &p, int out[4]);
 bool mid_plan(const LinearParams &p, int out[5]);
 // Raise a kernel's dynamic-LDS limit (a per-function, per-device attribute; set once).  Returns a hipError_t.
 int ensure_dynamic_lds(const void *kernel, size_t bytes);
+// compute units of the current device (256 where the query fails)
+int cu_count();
 // true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);

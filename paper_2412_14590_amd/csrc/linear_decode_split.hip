@@ -451,19 +451,6 @@ struct Plan {
     size_t lds_bytes;
 };
 
-int cu_count()
-{
-    static int n[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (n[dev] == 0) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        n[dev] = v;
-    }
-    return n[dev];
-}
-
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Blocks for the 8-bit and for the 4-bit quarter tiles (units8, units4 of them; an 8-bit one has

@@ -300,19 +300,6 @@ __global__ __launch_bounds__(NT) void linear_mid_kernel(LinearParams p, MidArgs 
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-int cu_count()
-{
-    static int n[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (n[dev] == 0) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        n[dev] = v;
-    }
-    return n[dev];
-}
-
 // Quarter tiles per virtual tile.  A wave's time per K step does not depend on how many of its 16
 // columns are in use, and two waves on one SIMD take turns, so fewer, fuller virtual tiles are
 // never slower: always 4.

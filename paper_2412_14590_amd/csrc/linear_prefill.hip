@@ -19,8 +19,8 @@
 //  * Issue order.  A group is TM*4 MFMA slots.  Tiles are processed in pairs (two independent
 //    accumulation chains, alternating); the float rescale of the PREVIOUS pair runs in the
 //    shadow of the current pair's MFMAs (8 vector instructions per MFMA is what the vector port
-//    sustains at full MFMA rate), and the A fragment of slot s+6 is requested at slot s (LDS
-//    latency is several MFMAs long).  The pipeline runs across group boundaries; the only
+//    sustains at full MFMA rate), and the A fragment of slot s+6 (s+4 with two token tiles per
+//    wave) is requested at slot s (LDS latency is several MFMAs long).  The pipeline runs across group boundaries; the only
 //    block-wide barrier sits in the middle of a group (slot TM*2), where the next group's
 //    activations are known to have landed and the stage of the previous group is released.
 //  * Group metadata (4 fp16 scales, 4 zero points) is fetched once per 4 groups.
@@ -35,8 +35,7 @@
 namespace mixllm {
 
 constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
-constexpr int DFRAG = 6;    // an A fragment is requested this many MFMA slots before its use
-constexpr int RING = 8;     // fragment registers (DFRAG + 2: the slot being overwritten is two MFMAs old)
+constexpr int RING = 8;     // fragment registers (at least DFRAG + 2: the slot being overwritten is two MFMAs old)
 
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
 template <int I, int N, typename F>
@@ -57,8 +56,13 @@ struct Shape {
     static constexpr int BN = WN * 32;            // channels per block
     static constexpr int A_STAGE = BM * G;        // bytes of one LDS stage
     static constexpr int LPW = BM / 8 / NW;       // direct-to-LDS loads (8 rows each) per wave and stage
+    // An A fragment is requested DFRAG MFMA slots before its use (LDS latency under load is several
+    // MFMAs).  Requests for the next group's stage must come after the barrier in the middle of the
+    // group (slot 2 TM), which is what tells a wave that the stage has landed for every wave.
+    static constexpr int DFRAG = TM >= 4 ? 6 : 2 * TM;
+    static_assert(TM * 4 - DFRAG >= TM * 2 && DFRAG + 2 <= RING, "fragment requests must not pass the barrier or wrap the ring");
     static_assert(BM % (8 * NW) == 0, "A tile must split evenly over the waves");
-    static_assert(TM % 4 == 0 && (TM * 4) % RING == 0, "an even number of tile pairs per group; slots wrap the fragment ring");
+    static_assert(TM % 2 == 0 && (TM * 4) % RING == 0, "token tiles go in pairs; slots wrap the fragment ring");
     static_assert((NSTAGE - 1) * A_STAGE + (TM * WM - 1) * 32 * G + 31 * G + 127 < 65536, "LDS offsets must fit 16 bits");
 };
 
@@ -71,9 +75,11 @@ struct Shape {
 template <typename C, bool DUMP, bool ACT_PT, bool PART8, bool ASYNC>
 static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a, float *lds_sa)
 {
-    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW;
+    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG;
     constexpr int NSLOT = TM * 4;            // MFMAs per group
     constexpr int HALF = NSLOT / 2;          // slot of the barrier
+    constexpr int PPS = 8 / (NSLOT - HALF);  // eighths of the next group's unpack per slot of the second half
+    static_assert(PPS * (NSLOT - HALF) == 8, "the unpack is spread evenly over the second half of the group");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int n32 = lane & 31, h = lane >> 5;
@@ -280,7 +286,8 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         __builtin_amdgcn_sched_barrier(0);
 
         static_for<0, NSLOT>([&](auto stc) {
-            constexpr int st = decltype(stc)::value, q = st / 8, j = (st % 8) / 2, i = st & 1, s = q & 1;
+            constexpr int st = decltype(stc)::value, q = st / 8, j = (st % 8) / 2, i = st & 1;
+            constexpr int s = (U * (TM / 2) + q) & 1;               // pairs alternate between the two accumulator sets, across groups too
             constexpr int mt = 2 * q + i;
             constexpr int qp = (q + TM / 2 - 1) % (TM / 2);         // pair being rescaled
             constexpr int up = 2 * qp + i;                         // ... its tile handled in this slot
@@ -313,8 +320,12 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
             P[s][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][j], j == 0 ? zero16 : P[s][i], 0, 0, 0);
             finish4(P[s ^ 1][i], std::integral_constant<int, up>{}, std::integral_constant<int, j>{},
                     q == 0 ? sw_prev : sw_cur, gp);
-            if constexpr (!PART8 && st >= HALF && st < HALF + 8)
-                unpack_piece(std::integral_constant<int, U + 1>{}, std::integral_constant<int, st - HALF>{}, zb_next);
+            if constexpr (!PART8 && st >= HALF) {
+                static_for<0, PPS>([&](auto ec) {
+                    unpack_piece(std::integral_constant<int, U + 1>{},
+                                 std::integral_constant<int, PPS * (st - HALF) + decltype(ec)::value>{}, zb_next);
+                });
+            }
             if (!DUMP) {
                 // issue order: MFMA, the LDS read(s), the vector instructions in its shadow
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -336,7 +347,8 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // the last pair of the last group is still waiting for its rescale
     static_for<0, 8>([&](auto tc) {
         constexpr int t = decltype(tc)::value, j = t / 2, i = t & 1, qp = TM / 2 - 1;
-        finish4(P[qp & 1][i], std::integral_constant<int, 2 * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last);
+        constexpr int s_last = (3 * (TM / 2) + qp) & 1;   // accumulator set of the last pair of a group with g & 3 == 3
+        finish4(P[s_last][i], std::integral_constant<int, 2 * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last);
     });
     // Drain: the last requests (clamped re-reads past the end of K) are still in flight, aimed at
     // this block's LDS and at registers nothing reads any more.  Tying those registers to the
@@ -377,9 +389,8 @@ template <typename C, bool ACT_PT>
 static __device__ inline void prefill_block_w8_channel_scale(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a,
                                                             float *lds_sa)
 {
-    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW;
+    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG;
     constexpr int NSLOT = TM * 4, HALF = NSLOT / 2;
-    static_assert(TM == 4, "slot -> (k step, token tile) mapping below assumes four token tiles");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int n32 = lane & 31, h = lane >> 5;
@@ -427,10 +438,10 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
     __syncthreads();
     v4i af[RING];
-    // slot t: k step t / 4, token tile t % 4
+    // slot t: k step t / TM, token tile t % TM
     auto load_frag = [&](auto stagec, auto tc) {
         constexpr int stage = decltype(stagec)::value, t = decltype(tc)::value;
-        af[t % RING] = *(const v4i *)(lds_a + a_rd[t / 4] + stage * A_STAGE + (t % 4) * 32 * G);
+        af[t % RING] = *(const v4i *)(lds_a + a_rd[t / TM] + stage * A_STAGE + (t % TM) * 32 * G);
     };
     static_for<0, DFRAG>([&](auto tc) { load_frag(std::integral_constant<int, 0>{}, tc); });
 
@@ -465,7 +476,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
                 load_frag(std::integral_constant<int, U>{}, std::integral_constant<int, st + DFRAG>{});
             else
                 load_frag(std::integral_constant<int, (U + 1) % NSTAGE>{}, std::integral_constant<int, st + DFRAG - NSLOT>{});
-            P[st % 4] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][st / 4], P[st % 4], 0, 0, 0);
+            P[st % TM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][st / TM], P[st % TM], 0, 0, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -592,7 +603,14 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
     if ((size_t)p.M * (size_t)p.K >= lim || (size_t)p.ntiles4 * TILE_N * (size_t)p.K / 2 >= lim ||
         (size_t)p.ntiles8 * TILE_N * (size_t)p.K >= lim)
         return (int)hipErrorInvalidValue;
-    // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower)
+    // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower).
+    // Where that grid has clearly less than one block per CU the chip is short of waves, not of rate:
+    // blocks of 64 x 128 (wave tile 64 x 32) double the waves and halve the chain of work each one
+    // runs.  Measured on K = 4096, N = 4096: 27.7 -> 18.6 us at M = 256 (64 blocks of 128 x 128),
+    // 29.1 -> 22.5 at M = 512 (128 blocks); K = 14336: 74.7 -> 50.9 and 78.0 -> 62.7; with 192 blocks
+    // (N = 6144, M = 512) the small blocks are 4 % slower, with 224 (N = 28672, M = 128) equal.
+    const long tiles128 = (long)((p.M + 127) / 128) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
+    if (3 * tiles128 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 2>, 2>(p, st);
     return launch_shape<Shape<1, 4, 4>, 2>(p, st);
 }
 
