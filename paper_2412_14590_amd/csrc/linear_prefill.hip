@@ -35,7 +35,6 @@
 namespace mixllm {
 
 constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
-constexpr int RING = 8;     // fragment registers (at least DFRAG + 2: the slot being overwritten is two MFMAs old)
 
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
 template <int I, int N, typename F>
@@ -47,7 +46,7 @@ static __device__ inline void static_for(F &&f)
     }
 }
 
-template <int WM_, int WN_, int TM_>
+template <int WM_, int WN_, int TM_, int WD_>
 struct Shape {
     static constexpr int WM = WM_, WN = WN_, TM = TM_;
     static constexpr int NW = WM * WN;
@@ -60,9 +59,12 @@ struct Shape {
     // MFMAs).  Requests for the next group's stage must come after the barrier in the middle of the
     // group (slot 2 TM), which is what tells a wave that the stage has landed for every wave.
     static constexpr int DFRAG = TM >= 4 ? 6 : 2 * TM;
+    static constexpr int RING = TM >= 2 ? 8 : 4;  // fragment registers (at least DFRAG + 2: the slot being overwritten is two MFMAs old)
+    static constexpr int NB = TM >= 2 ? 2 : 1;    // token tiles whose MFMA chains alternate (a bundle)
+    static constexpr int WD = WD_;                // groups between the request for packed 4-bit weights and the wait for them
     static_assert(TM * 4 - DFRAG >= TM * 2 && DFRAG + 2 <= RING, "fragment requests must not pass the barrier or wrap the ring");
     static_assert(BM % (8 * NW) == 0, "A tile must split evenly over the waves");
-    static_assert(TM % 2 == 0 && (TM * 4) % RING == 0, "token tiles go in pairs; slots wrap the fragment ring");
+    static_assert(TM % NB == 0 && (TM * 4) % RING == 0, "whole bundles of token tiles; slots wrap the fragment ring");
     static_assert((NSTAGE - 1) * A_STAGE + (TM * WM - 1) * 32 * G + 31 * G + 127 < 65536, "LDS offsets must fit 16 bits");
 };
 
@@ -75,8 +77,10 @@ struct Shape {
 template <typename C, bool DUMP, bool ACT_PT, bool PART8, bool ASYNC>
 static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a, float *lds_sa)
 {
-    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG;
+    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG, RING = C::RING;
     constexpr int NSLOT = TM * 4;            // MFMAs per group
+    constexpr int NB = C::NB, SB = 4 * NB;   // tiles and MFMA slots of a bundle
+    constexpr int NBG = TM / NB;             // bundles per group
     constexpr int HALF = NSLOT / 2;          // slot of the barrier
     constexpr int PPS = 8 / (NSLOT - HALF);  // eighths of the next group's unpack per slot of the second half
     static_assert(PPS * (NSLOT - HALF) == 8, "the unpack is spread evenly over the second half of the group");
@@ -126,9 +130,13 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     const uint32_t b_voff = PART8 ? ((uint32_t)tile16 * (uint32_t)(p.K / 64) * 64 + (n32 & 15) + 16 * h) * 16
                                   : ((uint32_t)tile16 * (uint32_t)ng * 64 + (n32 & 15) + 16 * h) * 16;
     v4i b[2][4];
-    v4i raw[2][2];
+    // packed 4-bit weights are requested WD groups before the wait for them (hand-issued loads
+    // only: with ordinary loads the wait below cannot count what is younger in the queue)
+    constexpr int WD = ASYNC ? C::WD : 1, NRAW = 2 * WD;
+    constexpr int NMETA = 2;   // load instructions of load_meta in the hand-issued variant
+    v4i raw[NRAW][2];
     auto load_b = [&](int g, auto setc) {
-        constexpr int set = decltype(setc)::value % 2;
+        constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW;
         const int gc = min(g, ng - 1);
         if (PART8) {
             const uint8_t *base = (const uint8_t *)p.w8 + (size_t)gc * 2048;
@@ -144,11 +152,11 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         } else {
             const uint8_t *base = p.w4 + (size_t)gc * 1024;
             if (ASYNC) {
-                load_reg16<0>(raw[set][0], b_voff, base);
-                load_reg16<512>(raw[set][1], b_voff, base);
+                load_reg16<0>(raw[rset][0], b_voff, base);
+                load_reg16<512>(raw[rset][1], b_voff, base);
             } else {
-                raw[set][0] = *(const v4i *)(base + b_voff);
-                raw[set][1] = *(const v4i *)(base + b_voff + 512);
+                raw[rset][0] = *(const v4i *)(base + b_voff);
+                raw[rset][1] = *(const v4i *)(base + b_voff + 512);
             }
         }
     };
@@ -184,10 +192,10 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     };
     // one eighth of the unpack of a group: raw dword d of `set` -> two operand dwords
     auto unpack_piece = [&](auto setc, auto dc, uint32_t zb) {
-        constexpr int set = decltype(setc)::value % 2, d = decltype(dc)::value;
+        constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW, d = decltype(dc)::value;
         constexpr int bj = d >> 1, e = d & 1;
         int lo, hi;
-        unpack_sub((uint32_t)raw[set][bj & 1][(bj >> 1) * 2 + e], zb, lo, hi);
+        unpack_sub((uint32_t)raw[rset][bj & 1][(bj >> 1) * 2 + e], zb, lo, hi);
         b[set][bj][2 * e] = lo;
         b[set][bj][2 * e + 1] = hi;
     };
@@ -230,7 +238,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     Meta meta_cur, meta_nxt;
     load_meta(0, meta_cur);
     load_b(0, std::integral_constant<int, 0>{});
-    if (!PART8) load_b(1, std::integral_constant<int, 1>{});
+    if (!PART8) static_for<1, WD + 1>([&](auto gc) { load_b(decltype(gc)::value, gc); });
     load_a(0, 0);
     load_a(1, 1);
     load_a(2, 2);
@@ -245,7 +253,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // everything above has landed (registers and LDS)
     await_loads<0>(meta_cur.s, meta_cur.z);
     if (PART8) await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
-    else await_loads<0>(raw[0][0], raw[0][1], raw[1][0], raw[1][1]);
+    else static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
     __syncthreads();
     meta_nxt = meta_cur;
     if (!PART8) {
@@ -256,18 +264,18 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // fragment of slot t of the group held in `stage`
     auto load_frag = [&](auto stagec, auto tc) {
         constexpr int stage = decltype(stagec)::value, t = decltype(tc)::value;
-        constexpr int mt = 2 * (t / 8) + (t & 1), j = (t % 8) / 2;
+        constexpr int mt = NB * (t / SB) + t % NB, j = (t % SB) / NB;
         af[t % RING] = *(const v4i *)(lds_a + a_rd[j] + stage * A_STAGE + mt * 32 * G);
     };
     static_for<0, DFRAG>([&](auto tc) { load_frag(std::integral_constant<int, 0>{}, tc); });
 
-    // int32 accumulators of the pair in flight (P[s]) and of the pair being rescaled (P[s^1])
-    v16i P[2][2];
+    // int32 accumulators of the bundle in flight (P[s]) and of the bundle being rescaled (P[s^1])
+    v16i P[2][NB];
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) P[s][i] = zero16;
-    float sw_prev = 0.0f;   // group scale of the pair left over from the previous group
+        for (int i = 0; i < NB; ++i) P[s][i] = zero16;
+    float sw_prev = 0.0f;   // group scale of the bundle left over from the previous group
 
     // one group; U = g & 3 selects the register sets and the LDS stage at compile time
     auto group_step = [&](int g, auto uc) {
@@ -286,11 +294,11 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         __builtin_amdgcn_sched_barrier(0);
 
         static_for<0, NSLOT>([&](auto stc) {
-            constexpr int st = decltype(stc)::value, q = st / 8, j = (st % 8) / 2, i = st & 1;
-            constexpr int s = (U * (TM / 2) + q) & 1;               // pairs alternate between the two accumulator sets, across groups too
-            constexpr int mt = 2 * q + i;
-            constexpr int qp = (q + TM / 2 - 1) % (TM / 2);         // pair being rescaled
-            constexpr int up = 2 * qp + i;                         // ... its tile handled in this slot
+            constexpr int st = decltype(stc)::value, q = st / SB, j = (st % SB) / NB, i = st % NB;
+            constexpr int s = (U * NBG + q) & 1;                   // bundles alternate between the two accumulator sets, across groups too
+            constexpr int mt = NB * q + i;
+            constexpr int qp = (q + NBG - 1) % NBG;                // bundle being rescaled
+            constexpr int up = NB * qp + i;                        // ... its tile handled in this slot
             const int gp = q == 0 ? g - 1 : g;                     // ... and its group
             if constexpr (st == HALF) {
                 // Middle of the group.  The wait leaves at most the LPW youngest loads in flight:
@@ -299,15 +307,19 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 // of group g+1's activations, group g+1's packed weights and the metadata.  After
                 // the barrier group g+1's activations are in LDS for every wave, and every wave is
                 // done reading the stage of group g-1, which the next request overwrites.
+                // (With WD = 2 the batch of the previous middle stays in flight as a whole: group
+                // g+2's packed weights, in front of them the metadata request if that middle made
+                // one, and the activations of group g+2.)
+                constexpr int YOUNGER = WD == 1 ? LPW : (U == 2 ? NMETA : 0) + 2 + LPW;
                 if (PART8) await_loads<LPW>();
-                else await_loads<LPW>(raw[(U + 1) % 2][0], raw[(U + 1) % 2][1]);
-                if constexpr (U == 3) await_loads<LPW>(meta_nxt.s, meta_nxt.z);
+                else await_loads<YOUNGER>(raw[(U + 1) % NRAW][0], raw[(U + 1) % NRAW][1]);
+                if constexpr (U == 3) await_loads<YOUNGER>(meta_nxt.s, meta_nxt.z);
                 if (!ACT_PT && !DUMP && tid < BM) lds_sa[((U + 1) % NSTAGE) * BM + tid] = sa_reg;
                 mid_group_barrier<(!ACT_PT && !DUMP)>();
                 if constexpr (U == 1) load_meta(g / 4 + 1, meta_nxt);
                 if (!ACT_PT && !DUMP && tid < BM)
                     sa_reg = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + min(g + 2, ng - 1)];
-                if (!PART8) load_b(g + 2, std::integral_constant<int, U + 2>{});
+                if (!PART8) load_b(g + 1 + WD, std::integral_constant<int, U + 1 + WD>{});
                 load_a(g + 3, (U + 3) % NSTAGE);
                 if (!PART8) zb_next = zbias(((U == 3 ? meta_nxt.z : meta_cur.z) >> (4 * ((U + 1) % 4))) & 15);
                 __builtin_amdgcn_sched_barrier(0);
@@ -344,17 +356,17 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         meta_cur = meta_nxt;
     }
     const int g_last = ((ng + 3) & ~3) - 1;   // group index the pending pair belongs to (may be a phantom one)
-    // the last pair of the last group is still waiting for its rescale
-    static_for<0, 8>([&](auto tc) {
-        constexpr int t = decltype(tc)::value, j = t / 2, i = t & 1, qp = TM / 2 - 1;
-        constexpr int s_last = (3 * (TM / 2) + qp) & 1;   // accumulator set of the last pair of a group with g & 3 == 3
-        finish4(P[s_last][i], std::integral_constant<int, 2 * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last);
+    // the last bundle of the last group is still waiting for its rescale
+    static_for<0, SB>([&](auto tc) {
+        constexpr int t = decltype(tc)::value, j = t / NB, i = t % NB, qp = NBG - 1;
+        constexpr int s_last = (3 * NBG + qp) & 1;   // accumulator set of the last bundle of a group with g & 3 == 3
+        finish4(P[s_last][i], std::integral_constant<int, NB * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last);
     });
     // Drain: the last requests (clamped re-reads past the end of K) are still in flight, aimed at
     // this block's LDS and at registers nothing reads any more.  Tying those registers to the
     // wait keeps them allocated until the data has arrived; without it they could be reused
     // (say for an epilogue address) and then be overwritten by a late load.
-    await_loads<0>(raw[0][0], raw[0][1], raw[1][0], raw[1][1]);
+    static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
     await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
     await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
     await_loads<0>(meta_nxt.s, meta_nxt.z);
@@ -389,7 +401,7 @@ template <typename C, bool ACT_PT>
 static __device__ inline void prefill_block_w8_channel_scale(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a,
                                                             float *lds_sa)
 {
-    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG;
+    constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG, RING = C::RING;
     constexpr int NSLOT = TM * 4, HALF = NSLOT / 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -605,13 +617,18 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
         return (int)hipErrorInvalidValue;
     // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower).
     // Where that grid has clearly less than one block per CU the chip is short of waves, not of rate:
-    // blocks of 64 x 128 (wave tile 64 x 32) double the waves and halve the chain of work each one
-    // runs.  Measured on K = 4096, N = 4096: 27.7 -> 18.6 us at M = 256 (64 blocks of 128 x 128),
-    // 29.1 -> 22.5 at M = 512 (128 blocks); K = 14336: 74.7 -> 50.9 and 78.0 -> 62.7; with 192 blocks
-    // (N = 6144, M = 512) the small blocks are 4 % slower, with 224 (N = 28672, M = 128) equal.
+    // blocks of 64 x 128 (wave tile 64 x 32) or 32 x 128 (wave tile 32 x 32) double the waves and
+    // halve the chain of work each one runs; their packed weights are requested two groups ahead
+    // (a group is too short to cover the latency; on the large tile two groups ahead measured no gain).
+    // Measured on K = 4096, N = 4096 with hot weights, 128 x 128 -> the shape chosen here: 26.5 -> 15 us
+    // at M = 128, 27.7 -> 16.2 at M = 256, 29.1 -> 22.5 at M = 512; K = 14336: 72.1 -> 39.8, 74.7 -> 44.8,
+    // 78.0 -> 62.7.  With 192 blocks of 128 x 128 (N = 6144, M = 512) the smaller blocks are 4 % slower,
+    // with 224 (N = 28672, M = 128) equal.
     const long tiles128 = (long)((p.M + 127) / 128) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
-    if (3 * tiles128 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 2>, 2>(p, st);
-    return launch_shape<Shape<1, 4, 4>, 2>(p, st);
+    const long tiles64 = (long)((p.M + 63) / 64) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
+    if (3 * tiles64 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 1, 2>, 2>(p, st);
+    if (3 * tiles128 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 2, 2>, 2>(p, st);
+    return launch_shape<Shape<1, 4, 4, 1>, 2>(p, st);
 }
 
 }  // namespace mixllm
