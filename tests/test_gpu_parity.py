@@ -130,7 +130,10 @@ def test_group_partials_bit_exact_small_m(M, K, N, n8, path):
 
 
 @pytest.mark.parametrize("M,K,N,n8", [(3, 256, 7, 2), (130, 512, 300, 30), (200, 1024, 530, 0), (33, 384, 70, 70),
-                                     (257, 256, 290, 29)])
+                                     (257, 256, 290, 29),
+                                     # grids that take the 64 x 128 and the 128 x 128 blocks (the smaller cases
+                                     # above run on 32 x 128 blocks), K not a multiple of 4 groups
+                                     (256, 384, 8192, 819), (384, 640, 8192, 0)])
 @pytest.mark.parametrize("path", ["generic", "prefill"])
 def test_group_partials_bit_exact_tiled(M, K, N, n8, path):
     say("partials", path, M, K, N, n8)
@@ -188,7 +191,7 @@ def test_linear_small_m(M, K, N, n8, path, variant):
 @pytest.mark.parametrize("variant", ["baseline", "paper"])
 @pytest.mark.parametrize("path", ["generic", "prefill"])
 @pytest.mark.parametrize("M,K,N,n8", [(17, 256, 7, 2), (130, 512, 300, 30), (200, 1024, 530, 0), (33, 384, 70, 70),
-                                     (512, 4096, 1024, 102)])
+                                     (512, 4096, 1024, 102), (256, 384, 8192, 819), (384, 640, 8192, 0)])
 def test_linear_tiled(M, K, N, n8, path, variant):
     check_linear(M, K, N, n8, path, variant)
 
