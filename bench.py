@@ -221,12 +221,17 @@ def main():
     copies = [packed0] + [[p.clone() for p in packed0] for _ in range(n_copies - 1)]
     log(f"[bench] packed weights {set_bytes / 1e6:.1f} MB per block, {n_copies} rotating copies")
 
+    # granularity of the scales: the measured default (one activation scale per token, one scale per
+    # 8-bit channel) or the paper's (both per group of 128, Sec. 4.1); the paper's gets a leg of its own
+    mode = {"copies": copies, "act_group": None, "w8_group": None}
+
     def make_acts(M):
         xs_ = [torch.from_numpy(synth.make_x(M, l.K, seed=7, tag="x/" + l.name)).to(dev) for l in layers]
         bufs = [(torch.empty((M, l.K), dtype=torch.int8, device=dev),
                  torch.empty((M, 1), dtype=torch.float16, device=dev),
                  torch.empty((M, l.N), dtype=torch.float16, device=dev),
-                 torch.empty(mx.query_sizes(M, l.K, l.N, l.n8)["workspace_bytes"], dtype=torch.uint8, device=dev))
+                 torch.empty(mx.query_sizes(M, l.K, l.N, l.n8, mode["act_group"], mode["w8_group"])["workspace_bytes"],
+                             dtype=torch.uint8, device=dev))
                 for l in layers]
         return xs_, bufs
 
@@ -239,11 +244,11 @@ def main():
         (executed if recording[0] is None else recording[0]).append(li)
 
     def step(i, xs_, bufs):
-        ws = copies[i % n_copies]
+        ws = mode["copies"][i % n_copies]
         for li in range(len(layers)):
             # the whole hot path from fp16 activations: one fused kernel where the library has one
-            # (a single token), otherwise activation quantizer + linear
-            mx.linear_fp16(xs_[li], ws[li], out=bufs[li][2], workspace=bufs[li][3])
+            # (a few tokens of a short row), otherwise activation quantizer + linear
+            mx.linear_fp16(xs_[li], ws[li], act_group=mode["act_group"], out=bufs[li][2], workspace=bufs[li][3])
             note(li)
 
     def time_steps(M, steps, warmup):
@@ -464,6 +469,20 @@ def main():
             other["roofline"] = {"bound": "hbm", "achieved": other["dominant_kernel"]["GBps"], "peak": HBM_PEAK_GBS,
                                  "unit": "GB/s", "frac": other["dominant_kernel"]["GBps"] / HBM_PEAK_GBS}
         result[key] = other
+        # the paper's granularity (activation scales per token and group, 8-bit weight scales per
+        # group): the whole step, same shapes, same launch method
+        packed_p = [mx.quantize_weights(torch.from_numpy(l.W).to(dev), l.salient_idx, w8_group=128) for l in layers]
+        mode.update(copies=[packed_p] + [[p.clone() for p in packed_p] for _ in range(n_copies - 1)],
+                    act_group=128, w8_group=128)
+        gran = []
+        for M in (1, 16, 2048):
+            small = M <= 16
+            sec = time_steps(M, 50 if small else 40, 5 if small else 40)
+            gran.append({"M": M, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9, "TOPS": step_ops(M) / sec / 1e12})
+            log(f"[bench] scales per group of 128 (activations and 8-bit weights), M={M}: {sec * 1e3:.4f} ms/step")
+        result["paper_granularity"] = {"act_group": 128, "w8_group": 128, "legs": gran,
+                                       "note": "GBps / TOPS use the algorithmic bytes / operations of the default granularity"}
+        mode.update(copies=copies, act_group=None, w8_group=None)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample ---------------------------
     if not args.no_cpu:

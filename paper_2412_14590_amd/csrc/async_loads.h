@@ -58,6 +58,11 @@ static __device__ inline void await_loads()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 template <int N>
+static __device__ inline void await_loads(uint32_t &a)
+{
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
+template <int N>
 static __device__ inline void await_loads(uint2 &a, uint32_t &b)
 {
     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");

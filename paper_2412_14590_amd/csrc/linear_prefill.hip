@@ -74,7 +74,7 @@ struct Shape {
 // instantiated with ASYNC use no scratch memory.)  Without ASYNC they are ordinary loads, which
 // the compiler awaits itself - later than necessary, because it does not see the hand-issued
 // activation loads ahead of them in the queue, but always correctly.
-template <typename C, bool DUMP, bool ACT_PT, bool PART8, bool ASYNC>
+template <typename C, bool DUMP, bool ACT_PT, bool PART8, bool PG8, bool ASYNC>
 static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a, float *lds_sa)
 {
     constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG, RING = C::RING;
@@ -92,7 +92,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     const int joff = PART8 ? 0 : p.n8;
     const int ng = p.ng;
     const int mw0 = wm * TM * 32;   // first row of this wave inside the block tile
-    const bool per_group_s8 = PART8 && !p.w8_per_channel;
+    constexpr bool per_group_s8 = PART8 && PG8;   // 8-bit tile with one weight scale per group
 
     // this lane's channel
     const int t16 = t16_0 + wn * 2 + (n32 >> 4);
@@ -227,7 +227,12 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
             for (int i = 0; i < 4; ++i) acc[mt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw, acc[mt][4 * j + i]);
         } else {
             // per-(token, group) activation scales of the tile's group, staged in LDS
-            const v4f sa = *(const v4f *)(lds_sa + ((gp + NSTAGE) % NSTAGE) * BM + mw0 + mt * 32 + 8 * j + 4 * h);
+            // (The offset goes through an empty asm statement so that the read stays in this MFMA
+            // slot: the compiler otherwise gathers the reads of half a group at its start and runs
+            // out of registers holding them.)
+            uint32_t sa_off = (uint32_t)((((gp + NSTAGE) % NSTAGE) * BM + mw0 + mt * 32 + 8 * j + 4 * h) * sizeof(float));
+            asm volatile("" : "+v"(sa_off));
+            const v4f sa = *(const v4f *)((const uint8_t *)lds_sa + sa_off);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 acc[mt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw * sa[i], acc[mt][4 * j + i]);
@@ -242,16 +247,23 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     load_a(0, 0);
     load_a(1, 1);
     load_a(2, 2);
-    float sa_reg = 0.0f;   // activation scale of (row tid, group g+1), on its way to LDS
-    if (!ACT_PT && !DUMP && tid < BM) {
+    // Activation scale (fp16 bits) of (token row tid, group g+1) on its way to LDS: every thread
+    // requests one (rows past the tile re-read its last row), so that all waves count the same loads.
+    uint32_t sa_bits = 0;
+    const uint32_t sa_voff = (uint32_t)min(m0 + min(tid, BM - 1), p.M - 1) * (uint32_t)ng * 2u;
+    const uint32_t lds_sa_thread = lds_address(lds_sa) + (uint32_t)min(tid, BM - 1) * (uint32_t)sizeof(float);   // this thread's cell of stage 0
+    if (!ACT_PT && !DUMP) {
+        if (tid < BM) {
 #pragma unroll
-        for (int s = 1; s < NSTAGE; ++s) lds_sa[s * BM + tid] = 0.0f;   // read (times a zero scale) before first written
-        lds_sa[tid] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng];
-        sa_reg = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + min(1, ng - 1)];
+            for (int s = 1; s < NSTAGE; ++s) lds_sa[s * BM + tid] = 0.0f;   // read (times a zero scale) before first written
+            lds_sa[tid] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng];
+        }
+        load_reg_u16(sa_bits, sa_voff, p.xscale + min(1, ng - 1));
     }
-    const float sw_row = (PART8 && !DUMP && p.w8_per_channel) ? (float)p.s8[rw] : 0.0f;
+    const float sw_row = (PART8 && !DUMP && !PG8) ? (float)p.s8[rw] : 0.0f;
     // everything above has landed (registers and LDS)
     await_loads<0>(meta_cur.s, meta_cur.z);
+    await_loads<0>(sa_bits);
     if (PART8) await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
     else static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
     __syncthreads();
@@ -310,15 +322,26 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 // (With WD = 2 the batch of the previous middle stays in flight as a whole: group
                 // g+2's packed weights, in front of them the metadata request if that middle made
                 // one, and the activations of group g+2.)
-                constexpr int YOUNGER = WD == 1 ? LPW : (U == 2 ? NMETA : 0) + 2 + LPW;
-                if (PART8) await_loads<LPW>();
+                // A batch is issued in the order metadata, activation scale, packed weights,
+                // activations; the scale request of the previous middle (group g+1's) is older than
+                // that middle's weights and activations, so with per-group activation scales the
+                // WD = 2 wait does not count a metadata request as young.  An 8-bit tile requests
+                // its weights at the start of a group: the 4 loads of group g+1 are the youngest.
+                constexpr int YOUNGER = PART8 ? LPW + 4 : WD == 1 ? LPW : (U == 2 && ACT_PT ? NMETA : 0) + 2 + LPW;
+                if (PART8) await_loads<YOUNGER>();
                 else await_loads<YOUNGER>(raw[(U + 1) % NRAW][0], raw[(U + 1) % NRAW][1]);
                 if constexpr (U == 3) await_loads<YOUNGER>(meta_nxt.s, meta_nxt.z);
-                if (!ACT_PT && !DUMP && tid < BM) lds_sa[((U + 1) % NSTAGE) * BM + tid] = sa_reg;
+                if (!ACT_PT && !DUMP) {
+                    await_loads<YOUNGER>(sa_bits);
+                    // every thread stores (threads past the tile repeat its last row's value): no
+                    // branch in the middle of the group, and a store the compiler does not have to
+                    // order against the fragment reads it has in flight
+                    const float sa_val = half_bits_to_float(sa_bits);
+                    asm volatile("ds_write_b32 %0, %1" ::"v"(lds_sa_thread + (uint32_t)(((U + 1) % NSTAGE) * BM * sizeof(float))), "v"(sa_val) : "memory");
+                }
                 mid_group_barrier<(!ACT_PT && !DUMP)>();
                 if constexpr (U == 1) load_meta(g / 4 + 1, meta_nxt);
-                if (!ACT_PT && !DUMP && tid < BM)
-                    sa_reg = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + min(g + 2, ng - 1)];
+                if (!ACT_PT && !DUMP) load_reg_u16(sa_bits, sa_voff, p.xscale + min(g + 2, ng - 1));
                 if (!PART8) load_b(g + 1 + WD, std::integral_constant<int, U + 1 + WD>{});
                 load_a(g + 3, (U + 3) % NSTAGE);
                 if (!PART8) zb_next = zbias(((U == 3 ? meta_nxt.z : meta_cur.z) >> (4 * ((U + 1) % 4))) & 15);
@@ -370,6 +393,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
     await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
     await_loads<0>(meta_nxt.s, meta_nxt.z);
+    await_loads<0>(sa_bits);
     if (DUMP) return;
 
     // ---- epilogue: token scale, fp16, scatter (Sec. 3.4) ------------------------------
@@ -547,14 +571,14 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
     const int r = L - bd * band * nb;
     const int bn = r / w, bm = bd * band + r % w;
     constexpr int T16 = C::BN / TILE_N;
-    constexpr bool ASYNC = W8PC && ACT_PT && !DUMP;   // the benchmarked variant; spill free (checked by the build)
+    constexpr bool ASYNC = !DUMP;   // every variant but the debug dump issues its loads by hand; spill free (checked by the build)
     if (part8) {
-        if constexpr (ASYNC)
+        if constexpr (W8PC && ACT_PT && !DUMP)
             prefill_block_w8_channel_scale<C, ACT_PT>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
         else
-            prefill_block<C, DUMP, ACT_PT, true, false>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+            prefill_block<C, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
     } else
-        prefill_block<C, DUMP, ACT_PT, false, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+        prefill_block<C, DUMP, ACT_PT, false, false, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
 }
 
 // The kernels take more dynamic LDS than the default limit; raising the limit is a per-function
@@ -604,7 +628,15 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
         return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, true>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     if (p.act_per_token)
         return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
-    return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+    // Per-(token, group) activation scales: built for one and two token tiles per wave.  With four
+    // the kernel needs more than 256 registers (the scale reads from LDS and the extra multiply
+    // come on top of 235), and a kernel with hand-issued loads must not spill.
+    if constexpr (C::TM <= 2) {
+        if (p.w8_per_channel)
+            return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, true>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+    }
+    return (int)hipErrorInvalidValue;
 }
 
 int launch_linear_prefill(const LinearParams &p, hipStream_t st)
@@ -627,7 +659,7 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
     const long tiles128 = (long)((p.M + 127) / 128) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
     const long tiles64 = (long)((p.M + 63) / 64) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
     if (3 * tiles64 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 1, 2>, 2>(p, st);
-    if (3 * tiles128 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 2, 2>, 2>(p, st);
+    if (3 * tiles128 <= 2 * cu_count() || (!p.act_per_token && !p.P)) return launch_shape<Shape<1, 4, 2, 2>, 2>(p, st);
     return launch_shape<Shape<1, 4, 4, 1>, 2>(p, st);
 }
 
