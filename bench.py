@@ -454,7 +454,7 @@ def main():
     # ---- extra legs ------------------------------------------------------------------------
     if not args.no_extras:
         sweep = []
-        for M in ([2, 4, 8, 16, 64, 256] if decode_like else [512]):
+        for M in ([2, 4, 8, 16, 64, 256] if decode_like else [512, 8192]):
             small = M <= 16
             sweep.append(leg(M, max(20, args.steps // 4) if small else 40, 5 if small else 40, 50 if small else 30))
         other = leg(2048 if decode_like else 1, 40 if decode_like else 100, 40 if decode_like else 3, 30)
