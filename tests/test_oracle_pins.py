@@ -362,7 +362,7 @@ def test_paper_roofline_constants():
 
 
 def test_config0_shape_runs_and_matches_bruteforce_on_sampled_columns():
-    # BASELINE config 0: M=1, K=N=4096, 410 int8 rows.  Full oracle run, checked on a column sample.
+    # The single-layer workload: M=1, K=N=4096, 410 int8 rows.  Full oracle run, checked on a column sample.
     lay = synth.make_layer("o", 4096, 4096, seed=0)
     assert lay.n8 == 410 and len(lay.salient_idx) == 410
     L = ref.quantize_weights(lay.W, lay.salient_idx)
