@@ -291,6 +291,46 @@ def test_output_permutation_and_determinism():
 
 # ------------------------------------------------ full-size layers of the workloads --
 
+def test_random_shapes_through_every_path_that_covers_them():
+    """60 seeded random shapes (tokens 1..299, K of 1..40 groups, ragged N, any 8-bit share, both scale
+    granularities): AUTO, the tiled kernel, every decode variant, the kernel for a few dozen tokens and
+    the fp16 entry point, partials bit-exact and outputs within tolerance wherever a path takes the shape."""
+    rng = np.random.default_rng(20241)
+    for it in range(60):
+        kind = rng.integers(0, 4)
+        M = int(rng.integers(1, 17)) if kind == 0 else int(rng.integers(17, 65)) if kind == 1 else \
+            int(rng.integers(65, 300)) if kind == 2 else int(rng.choice([1, 2, 3, 4, 8, 16, 32, 64, 128, 129, 256]))
+        K = 128 * int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 28, 32, 40]))
+        N = int(rng.choice([1, 5, 16, 17, 33, 100, 130, 500, 1030, 2070]))
+        while M * K * N > 1.5e8:
+            N = max(1, N // 2)
+        n8 = int(rng.choice([0, N, N // 10, int(rng.integers(0, N + 1))]))
+        ag, wg = (128, 128) if rng.integers(0, 3) == 0 else (None, None)
+        _, _, L, x, xq, xs = make_case(M, K, N, n8, seed=5000 + it, w8_group=wg, act_group=ag)
+        PL = pack_from_oracle(L)
+        y_ref = ref.mixed_linear(xq, xs, L)
+        P_ref = ref.group_partials(xq, L)
+        paths = ["generic", "prefill"] + (DECODE_VARIANTS if M <= 16 else []) + (["mid"] if M <= 64 else [])
+        taken = 0
+        for name in [None] + paths:
+            path = mx.PATH_AUTO if name is None else PATHS[name]
+            try:
+                y = mx.mixed_linear(dev(xq), dev(xs), PL, path)
+                P = mx.debug_group_partials(dev(xq), PL, path)
+            except mx.MixllmError as e:
+                assert e.status == -2 and name in ("decode_split", "mid"), (name, M, K, N, n8)   # EUNSUPPORTED
+                continue
+            torch.cuda.synchronize()
+            taken += 1
+            assert np.array_equal(P.cpu().numpy(), P_ref), (name, M, K, N, n8, ag)
+            assert row_rel_err(y.cpu().numpy(), y_ref) <= TOL, (name, M, K, N, n8, ag)
+        assert taken >= 3
+        yf = mx.linear_fp16(dev(x), PL, act_group=ag)
+        torch.cuda.synchronize()
+        assert row_rel_err(yf.cpu().numpy(), y_ref) <= TOL, ("fp16 entry", M, K, N, n8, ag)
+    say("  60 random shapes: all paths agree with the oracle")
+
+
 @pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
 def test_llama3_8b_decode_layers_full_size(name):
     K, N = synth.LLAMA3_8B[name]
