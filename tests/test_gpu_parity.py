@@ -110,6 +110,39 @@ def test_pack_unpack_round_trip_and_padding_is_zero(K, N, n8, w8_group):
         assert torch.equal(getattr(P, k), getattr(Q, k)), k
 
 
+def test_quantizers_on_random_shapes_and_value_ranges():
+    """40 seeded random cases for the two quantizers: ragged N, K of 1..40 groups, any 8-bit share, both
+    granularities, value scales from 1e-4 to 1e3 (fp16 subnormal scales up to near overflow): codes,
+    zero points, scales and the channel order bit-exact against the oracle."""
+    rng = np.random.default_rng(20242)
+    for it in range(40):
+        K = 128 * int(rng.choice([1, 2, 3, 5, 8, 16, 28, 40]))
+        N = int(rng.choice([1, 3, 16, 17, 47, 100, 257, 1000]))
+        n8 = int(rng.choice([0, N, N // 10, int(rng.integers(0, N + 1))]))
+        M = int(rng.choice([1, 2, 7, 16, 33, 130]))
+        wg = 128 if rng.integers(0, 2) else None
+        ag = 128 if rng.integers(0, 2) else None
+        scale = float(10.0 ** rng.uniform(-4, 3))
+        W, sal, _, x, _, _ = make_case(M, K, N, n8, seed=7000 + it, w8_group=wg, act_group=ag)
+        W = (W.astype(np.float32) * (scale / 0.02)).clip(-60000, 60000).astype(np.float16)
+        x = (x.astype(np.float32) * scale).clip(-60000, 60000).astype(np.float16)
+        L = ref.quantize_weights(W, sal, G, wg)
+        u = mx.unpack_weights(mx.quantize_weights(dev(W), sal, wg))
+        tag = (K, N, n8, wg, scale)
+        assert np.array_equal(u["perm"].cpu().numpy(), L.perm), tag
+        if L.n8:
+            assert np.array_equal(u["s8"].cpu().numpy().view(np.uint16), L.s8.view(np.uint16)), tag
+            assert np.array_equal(u["q8"].cpu().numpy(), L.q8), tag
+        if L.n4:
+            assert np.array_equal(u["s4"].cpu().numpy().view(np.uint16), L.s4.view(np.uint16)), tag
+            assert np.array_equal(u["z4"].cpu().numpy(), L.z4), tag
+            assert np.array_equal(u["q4"].cpu().numpy(), L.q4), tag
+        xq_ref, xs_ref = ref.quantize_act(x, ag)
+        xq, xs = mx.quantize_activations(dev(x), ag)
+        assert np.array_equal(xs.cpu().numpy().view(np.uint16), xs_ref.view(np.uint16)), (M, K, ag, scale)
+        assert np.array_equal(xq.cpu().numpy(), xq_ref), (M, K, ag, scale)
+
+
 # ------------------------------------------------------------ integer partial sums --
 
 def check_partials(M, K, N, n8, path, seed=24):
