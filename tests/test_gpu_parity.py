@@ -324,6 +324,29 @@ def test_output_permutation_and_determinism():
 
 # ------------------------------------------------ full-size layers of the workloads --
 
+@pytest.mark.parametrize("M", [1, 16, 40, 130])
+def test_outputs_beyond_the_fp16_range_become_infinities(M):
+    # the conversion of an output that does not fit fp16 is the IEEE one (to +-inf), in the oracle and
+    # in every kernel; finite outputs next to them still agree
+    K, N, n8 = 512, 48, 5
+    W = np.zeros((N, K), dtype=np.float16)
+    W[:, :] = np.float16(0.01)
+    W[3, :] = np.float16(30.0)       # a 4-bit row and (below) an 8-bit row with huge outputs
+    W[7, :] = np.float16(-25.0)
+    sal = np.array([7, 11, 20, 33, 40], dtype=np.int32)
+    x = np.full((M, K), 20.0, dtype=np.float16)
+    L = ref.quantize_weights(W, sal, G, None)
+    xq, xs = ref.quantize_act(x, None)
+    y_ref = ref.mixed_linear(xq, xs, L)
+    assert np.isinf(y_ref[:, 3]).all() and np.isinf(y_ref[:, 7]).all() and np.isfinite(y_ref[:, 0]).all()
+    for path in (mx.PATH_AUTO, mx.PATH_PREFILL, mx.PATH_GENERIC):
+        y = mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), path).cpu().numpy()
+        assert np.array_equal(np.isinf(y), np.isinf(y_ref))
+        assert np.array_equal(np.sign(y[np.isinf(y)]), np.sign(y_ref[np.isinf(y_ref)]))
+        fin = np.isfinite(y_ref)
+        assert np.allclose(y[fin].astype(np.float64), y_ref[fin].astype(np.float64), rtol=2e-3)
+
+
 def test_random_shapes_through_every_path_that_covers_them():
     """60 seeded random shapes (tokens 1..299, K of 1..40 groups, ragged N, any 8-bit share, both scale
     granularities): AUTO, the tiled kernel, every decode variant, the kernel for a few dozen tokens and
