@@ -493,7 +493,7 @@ def main():
         log(f"[bench] oracle weight quantization {time.time() - t1:.1f}s (not timed)")
         xs_h = [synth.make_x(Ms, l.K, seed=7, tag="x/" + l.name) for l in layers]
         reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 50:
+        while t_cpu < 10.0 and reps < 5000:
             t = time.perf_counter()
             for xh, L in zip(xs_h, Ls):
                 xq, xsc = ref.quantize_act(xh)
