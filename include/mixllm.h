@@ -175,9 +175,8 @@ int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xsca
  * fp16 outputs in the original channel order out):
  *   x fp16 [M][K] -> y fp16 [M][N], same definition as mixllm_quantize_activations followed by
  *   mixllm_mixed_linear (the same codes and scales; the fp32 sums may be taken in another order).
- * For one token (K <= 4096, or K <= 16384 with one activation scale per token) and for up to 16
- * tokens of a short row (M K <= 16384, K a multiple of 512, one scale per token) this is ONE
- * kernel: every block of the decode kernel quantizes the activations itself while its first
+ * For up to 16 tokens with M K <= 16384 (several tokens with one activation scale per token: K a
+ * multiple of 512) this is ONE kernel: every block of the decode kernel quantizes the activations itself while its first
  * weight loads are in flight, and `workspace` is not touched (may be NULL).  Otherwise the two
  * kernels run back to back on `stream` with xq and xscale placed in `workspace` (at least
  * mixllm_query_sizes().workspace_bytes, 16-byte aligned).

@@ -220,9 +220,9 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     for (int vt = 0; vt < nvt; ++vt)
 #pragma unroll
         for (int r = 0; r < NR; ++r) red[((vt * NW + wave) * NR + r) * 64 + lane] = 0.0f;
-    if (!ACT_PT && !DUMP)
+    if (!ACT_PT && !DUMP && !FUSED)
         for (int i = tid; i < p.M * ng; i += NT) xsg[i] = (float)p.xscale[i];
-    if (FUSED == 2) {
+    if (FUSED == 2 && ACT_PT) {
         if (tid < 16) tokmax[tid] = 0u;
         lds_barrier();   // while the activations are still on their way
     }
@@ -231,7 +231,37 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
         if (j * NT < npiece) await_vec<(D - 1) * NL>(xv[j]);
 
     // ---- 2. stage the activations ----
-    if (FUSED == 2) {
+    if (FUSED && !ACT_PT) {
+        // One scale per (token, group): the 16 lanes that hold a group of 128 values find its
+        // maximum among themselves (K is a multiple of 128, so such a run of 16 pieces lies in
+        // one token row and one group, and is loaded completely or not at all).
+        const int per_row = p.K / 8;
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j) {
+            const int i = tid + NT * j;
+            if (j * NT < npiece) {
+                const h8 hv = __builtin_bit_cast(h8, xv[j]);   // the whole register, after its wait
+                float amax = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf((float)hv[e]));
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+                const float sc = (float)store_scale(amax / 127.0f);
+                const float rc = recip(sc);
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    w0 |= quant_code(hv[e], sc, rc) << (8 * e);
+                    w1 |= quant_code(hv[4 + e], sc, rc) << (8 * e);
+                }
+                if (i < npiece) {
+                    const int tok = i / per_row, pos = i - tok * per_row;
+                    *(uint2 *)(lds_x + tok * xstride + pos * 8) = make_uint2(w0, w1);
+                    if ((lane & 15) == 0) xsg[tok * ng + (pos >> 4)] = sc;
+                }
+            }
+        }
+    } else if (FUSED == 2) {
         // Several tokens.  K is a multiple of 512, so the 64 pieces of one load of a wave lie in
         // one token row: the wave reduces their maximum and one lane folds it into the row's
         // cell (non-negative floats order like their bit patterns).
@@ -478,12 +508,12 @@ bool compute_plan(const LinearParams &p, Plan &o)
 {
     if (p.M < 1 || p.M > 16 || p.ng < 1) return false;
     const bool fused = p.x != nullptr;
-    // fp16 activations: per-token scales only, at most 4 loads per thread (16 Ki values); several
-    // tokens need K = a multiple of 512.  Every block repeats the quantizer: measured on the
+    // fp16 activations: at most 4 loads per thread (16 Ki values); several tokens with one scale
+    // per token need K = a multiple of 512.  Every block repeats the quantizer: measured on the
     // Llama-3-8B block, 16 Ki values cost as much as the stand-alone kernel they replace
     // (52.2 against 52.7 us per step at M = 4), 32 Ki values much more (68.0 against 57.7 at M = 8).
-    if (fused && (!p.act_per_token || p.P || (size_t)p.M * p.K > (size_t)NT * 8 * 4)) return false;
-    if (fused && p.M > 1 && p.K % 512 != 0) return false;
+    if (fused && (p.P || (size_t)p.M * p.K > (size_t)NT * 8 * 4)) return false;
+    if (fused && p.act_per_token && p.M > 1 && p.K % 512 != 0) return false;
     if (!fused && (size_t)p.M * p.K > (size_t)NT * 16 * 16) return false;
     o.nr = p.M <= 4 ? 1 : 4;
     const int nquads = (p.ng + 3) / 4;
@@ -553,6 +583,7 @@ int launch_nr(const LinearParams &p, const SplitArgs &a, size_t lds_bytes, hipSt
         return (int)hipGetLastError();
     };
     if (p.P) return go(linear_decode_split_kernel<NR, true, true, 0>);
+    if (p.x && !p.act_per_token) return go(linear_decode_split_kernel<NR, false, false, 2>);
     if (p.x && p.M > 1) return go(linear_decode_split_kernel<NR, false, true, 2>);
     if (p.x) {
         if constexpr (NR == 1) return go(linear_decode_split_kernel<1, false, true, 1>);
