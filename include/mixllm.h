@@ -244,8 +244,11 @@ int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream);
  * of `d` over its blocks.  path = MIXLLM_PATH_DECODE_SPLIT: plan[0..3] = blocks of the 8-bit part,
  * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS;
  * path = MIXLLM_PATH_MID: plan[0..4] = blocks of the 8-bit part, of the 4-bit part, quarter tiles
- * per virtual tile of the 8-bit and of the 4-bit part, bytes of LDS.  plan must hold 8 ints.
- * Returns EUNSUPPORTED when the path does not cover the shape, EINVAL for other paths.
+ * per virtual tile of the 8-bit and of the 4-bit part, bytes of LDS; path = MIXLLM_PATH_PREFILL:
+ * plan[0..7] = token rows and channels of a block tile, token tiles, channel tiles of the 8-bit and
+ * of the 4-bit part, blocks launched, token tiles per band of the block order, bytes of LDS.  plan
+ * must hold 8 ints.  Returns EUNSUPPORTED when the path does not cover the shape, EINVAL for other
+ * paths.
  */
 int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan);
 

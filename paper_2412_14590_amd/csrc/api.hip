@@ -385,6 +385,7 @@ int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan)
     bool ok;
     if (path == MIXLLM_PATH_DECODE_SPLIT) ok = decode_split_plan(p, out);
     else if (path == MIXLLM_PATH_MID) ok = mid_plan(p, out);
+    else if (path == MIXLLM_PATH_PREFILL) ok = prefill_plan(p, out);
     else return MIXLLM_EINVAL;
     if (!ok) return MIXLLM_EUNSUPPORTED;
     for (int i = 0; i < 8; ++i) plan[i] = out[i];

@@ -152,6 +152,7 @@ int cu_count();
 // true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);
+bool prefill_plan(const LinearParams &p, int out[8]);
 // path for 17..128 tokens (linear_mid.hip)
 bool mid_covers(const LinearParams &p);
 int launch_linear_mid(const LinearParams &p, hipStream_t st);

@@ -613,15 +613,29 @@ static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStre
     return (int)hipGetLastError();
 }
 
+// the grid of a launch: token tiles, channel tiles of either part, logical block ids per XCD of
+// either part, token tiles per band (see linear_prefill_kernel)
+struct PrefillGrid {
+    int nbm, nb8, nb4, per4, per8, band;
+};
+static PrefillGrid grid_of(const LinearParams &p, int BM, int BN)
+{
+    PrefillGrid g;
+    g.nbm = (p.M + BM - 1) / BM;
+    g.nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN;
+    g.nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
+    g.per4 = (g.nbm * g.nb4 + 7) / 8;
+    g.per8 = (g.nbm * g.nb8 + 7) / 8;
+    g.band = min(4, g.nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
+    return g;
+}
+
 template <typename C, int MINW>
 static int launch_shape(const LinearParams &p, hipStream_t st)
 {
-    constexpr int BM = C::BM, BN = C::BN;
-    const int nbm = (p.M + BM - 1) / BM;
-    const int nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN, nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
-    const int per4 = (nbm * nb4 + 7) / 8, per8 = (nbm * nb8 + 7) / 8;
+    const PrefillGrid gr = grid_of(p, C::BM, C::BN);
+    const int nbm = gr.nbm, nb8 = gr.nb8, nb4 = gr.nb4, per4 = gr.per4, per8 = gr.per8, band = gr.band;
     dim3 grid((per4 + per8) * 8), block(C::THREADS);
-    const int band = min(4, nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
     if (p.P)
         return launch_variant<C>(linear_prefill_kernel<C, MINW, true, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     if (p.act_per_token && p.w8_per_channel)
@@ -637,6 +651,16 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
         return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     }
     return (int)hipErrorInvalidValue;
+}
+
+// token tiles (of 32) per wave: 4 = blocks of 128 x 128, 2 = 64 x 128, 1 = 32 x 128
+static int token_tiles_per_wave(const LinearParams &p)
+{
+    const long nbn = (p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
+    const long tiles128 = (long)((p.M + 127) / 128) * nbn, tiles64 = (long)((p.M + 63) / 64) * nbn;
+    if (3 * tiles64 <= 2 * cu_count()) return 1;
+    if (3 * tiles128 <= 2 * cu_count() || (!p.act_per_token && !p.P)) return 2;
+    return 4;
 }
 
 int launch_linear_prefill(const LinearParams &p, hipStream_t st)
@@ -656,11 +680,31 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
     // at M = 128, 27.7 -> 16.2 at M = 256, 29.1 -> 22.5 at M = 512; K = 14336: 72.1 -> 39.8, 74.7 -> 44.8,
     // 78.0 -> 62.7.  With 192 blocks of 128 x 128 (N = 6144, M = 512) the smaller blocks are 4 % slower,
     // with 224 (N = 28672, M = 128) equal.
-    const long tiles128 = (long)((p.M + 127) / 128) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
-    const long tiles64 = (long)((p.M + 63) / 64) * ((p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128);
-    if (3 * tiles64 <= 2 * cu_count()) return launch_shape<Shape<1, 4, 1, 2>, 2>(p, st);
-    if (3 * tiles128 <= 2 * cu_count() || (!p.act_per_token && !p.P)) return launch_shape<Shape<1, 4, 2, 2>, 2>(p, st);
-    return launch_shape<Shape<1, 4, 4, 1>, 2>(p, st);
+    switch (token_tiles_per_wave(p)) {
+    case 1: return launch_shape<Shape<1, 4, 1, 2>, 2>(p, st);
+    case 2: return launch_shape<Shape<1, 4, 2, 2>, 2>(p, st);
+    default: return launch_shape<Shape<1, 4, 4, 1>, 2>(p, st);
+    }
+}
+
+// the launch plan as eight integers (token rows and channels of a block tile, token tiles, channel
+// tiles of the 8-bit and of the 4-bit part, blocks launched, token tiles per band, bytes of LDS), for
+// the host-side test of the block -> tile mapping
+bool prefill_plan(const LinearParams &p, int out[8])
+{
+    if (p.M < 1 || p.N < 1) return false;
+    const int tm = token_tiles_per_wave(p);
+    const int BM = 32 * tm, BN = 128;
+    const PrefillGrid g = grid_of(p, BM, BN);
+    out[0] = BM;
+    out[1] = BN;
+    out[2] = g.nbm;
+    out[3] = g.nb8;
+    out[4] = g.nb4;
+    out[5] = (g.per4 + g.per8) * 8;
+    out[6] = g.band;
+    out[7] = NSTAGE * BM * G + ((!p.act_per_token && !p.P) ? NSTAGE * BM * (int)sizeof(float) : 16);
+    return true;
 }
 
 }  // namespace mixllm

@@ -121,4 +121,63 @@ def test_mid_plan_covers_every_channel_once(K, N, n8):
         check_mid_part(t8, nblk8, qv8)
         check_mid_part(t4, nblk4, qv4)
     assert plan(mx.PATH_MID, 65, K, N, n8)[0] == -2
-    assert plan(mx.PATH_PREFILL, 64, K, N, n8)[0] == -1
+
+
+def check_prefill_grid(M, K, N, n8, act_group=None):
+    """linear_prefill.hip: blocks are dealt round robin to 8 XCDs; per XCD a contiguous range of 4-bit
+    logical ids, then of 8-bit ids; ids walk the tile grid in bands of `band` token tiles (channel
+    tile outer, token tile inner).  Restated here: every (token tile, channel tile) of either part
+    must be taken by exactly one block, and no block may name a tile outside the grid."""
+    out = (C.c_int32 * 8)()
+    d = binding._desc(M, K, N, n8, act_group, None)
+    rc = mx.lib().mixllm_debug_work_split(C.byref(d), mx.PATH_PREFILL, C.cast(out, C.c_void_p))
+    assert rc == 0
+    BM, BN, nbm, nb8, nb4, blocks, band, lds = list(out)
+    t8, t4 = tiles(N, n8)
+    assert BM in (32, 64, 128) and BN == 128
+    assert nbm == -(-M // BM) and nb8 == -(-t8 * 16 // BN) and nb4 == -(-t4 * 16 // BN)
+    assert 1 <= band <= min(4, nbm) and lds <= 80 * 1024 and blocks % 8 == 0
+    # the shape rule: the largest block tile whose grid still has about one block per CU or more
+    nbn = nb8 + nb4
+    if act_group == 128:
+        assert BM <= 64
+    per4, per8 = -(-nbm * nb4 // 8), -(-nbm * nb8 // 8)
+    assert blocks == 8 * (per4 + per8)
+    seen = set()
+    for b in range(blocks):
+        xcd, i = b & 7, b >> 3
+        part8 = i >= per4
+        nb = nb8 if part8 else nb4
+        L = xcd * per8 + (i - per4) if part8 else xcd * per4 + i
+        if L >= nbm * nb:
+            continue
+        bd = L // (band * nb)
+        w = min(band, nbm - bd * band)
+        r = L - bd * band * nb
+        bn, bm = r // w, bd * band + r % w
+        assert 0 <= bm < nbm and 0 <= bn < nb, (b, bm, bn)
+        key = (part8, bm, bn)
+        assert key not in seen
+        seen.add(key)
+    assert len(seen) == nbm * (nb8 + nb4)
+    return BM
+
+
+@pytest.mark.parametrize("K,N,n8", SHAPES)
+def test_prefill_grid_covers_every_tile_once(K, N, n8):
+    sizes = set()
+    for M in (1, 31, 64, 65, 128, 200, 256, 512, 1000, 2048, 8192):
+        sizes.add(check_prefill_grid(M, K, N, n8))
+        check_prefill_grid(M, K, N, n8, act_group=128)
+    assert sizes <= {32, 64, 128}
+
+
+def test_prefill_block_tile_follows_the_grid_size():
+    # Llama-3-8B shapes on a 256-CU part (the fallback count without a GPU is also 256): small grids take
+    # small block tiles, the large prefill batches the 128 x 128 tile
+    assert check_prefill_grid(64, 4096, 4096, 410) == 32
+    assert check_prefill_grid(256, 4096, 4096, 410) == 32
+    assert check_prefill_grid(512, 4096, 4096, 410) == 64
+    assert check_prefill_grid(2048, 4096, 4096, 410) == 128
+    assert check_prefill_grid(128, 4096, 28672, 2867) == 128
+    assert check_prefill_grid(2048, 4096, 28672, 2867, act_group=128) == 64
