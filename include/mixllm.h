@@ -15,9 +15,10 @@
  *     return means nothing ran.  No function throws.
  *   - Unless a parameter says "host", every data pointer is DEVICE memory, owned by
  *     the caller, 16-byte aligned, of the size mixllm_query_sizes() reports.  The
- *     library allocates no device memory and keeps no state between calls.
+ *     library allocates no memory and keeps no state between calls.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
- *     enqueued on it and the call returns without synchronizing, except where stated.
+ *     enqueued on it and the call returns without synchronizing and without blocking
+ *     copies: no entry point waits for the device.
  *   - fp16 values are IEEE binary16, stored as 2-byte words.
  *   - Inputs holding Inf or NaN are not supported (results unspecified, no fault).
  *
@@ -39,6 +40,9 @@ extern "C" {
 #endif
 
 #define MIXLLM_GROUP 128
+/* Largest K: an 8-bit channel with one scale keeps a single int32 sum over all of K, and
+ * K * 127 * 127 must stay below 2^31. */
+#define MIXLLM_MAX_K 131072
 
 enum {
     MIXLLM_OK = 0,
@@ -58,12 +62,17 @@ enum {
     MIXLLM_PATH_DECODE_STREAM = 4,   /* a wave per tile (or per K part of a tile), activations re-read per tile */
     MIXLLM_PATH_DECODE_RESIDENT = 5, /* activation fragments kept in registers; falls back to STREAM where it cannot run */
     MIXLLM_PATH_DECODE_SPLIT = 6,    /* equal byte shares per block, activations in LDS; EUNSUPPORTED where it cannot run */
-    MIXLLM_PATH_MID = 7              /* weight-streaming path for a few dozen tokens, M <= 64; EUNSUPPORTED where it cannot run */
+    MIXLLM_PATH_MID = 7,             /* weight-streaming path for a few dozen tokens, M <= 64; EUNSUPPORTED where it cannot run */
+    /* the tiled path with the block shape chosen by the caller instead of by the grid size, for tests
+       and benchmarks: 32, 64 or 128 token rows x 128 channels */
+    MIXLLM_PATH_PREFILL_32 = 8,
+    MIXLLM_PATH_PREFILL_64 = 9,
+    MIXLLM_PATH_PREFILL_128 = 10     /* EUNSUPPORTED with one activation scale per (token, group) */
 };
 
 typedef struct mixllm_desc {
     int32_t M;         /* tokens (rows of x and y); may be 0 for the offline calls */
-    int32_t K;         /* input features, multiple of 128 */
+    int32_t K;         /* input features, multiple of 128, at most MIXLLM_MAX_K */
     int32_t N;         /* output features */
     int32_t n8;        /* how many of the N output channels are int8, 0..N */
     int32_t group;     /* quantization group size along K for the uint4 part: must be 128 */
@@ -99,7 +108,9 @@ const char *mixllm_status_string(int status);
 /* Library/ABI version, bumped when a packed layout or a signature changes. */
 int mixllm_abi_version(void);
 
-/* Pure host arithmetic; never touches the GPU.  Errors: EINVAL (null), EUNSUPPORTED (dims). */
+/* Sizes of the buffers of one layer in the packed layouts described above (footprints of Sec. 3.5:
+ * 0.5 + 2.5/G bytes per 4-bit weight, 1 + 2/G per 8-bit weight with group-wise scales).
+ * Pure host arithmetic; never touches the GPU.  Errors: EINVAL (null), EUNSUPPORTED (dims). */
 int mixllm_query_sizes(const mixllm_desc *d, mixllm_sizes *out);
 
 /*
@@ -115,22 +126,29 @@ int mixllm_build_feature_perm(int32_t N, int32_t n8, const int32_t *salient_idx_
  * Offline weight quantization and packing (Sec. 2 quantizer; configuration of Sec. 3.1.2 and
  * Sec. 4.1; ahead-of-time layout prepacking, Sec. 3.3 last paragraph).
  *   W            fp16 [N][K] row-major, device
- *   salient_idx  HOST int32 [n8]: the channels to keep at 8 bits (the per-layer slice of
- *                the global search result, Alg. 1; choosing them is the caller's business)
+ *   salient_idx  DEVICE int32 [n8] (4-byte aligned; may be NULL when n8 = 0): the channels to
+ *                keep at 8 bits, distinct, in [0, N), in any order - the per-layer slice of the
+ *                global search result (Alg. 1), i.e. what mixllm_select_salient leaves in
+ *                `selected`; choosing them is the caller's business.  The list stays on the
+ *                device, so its contents are not validated: an index outside [0, N) is ignored,
+ *                a repeated one counts once, and with fewer than n8 distinct valid entries the
+ *                order of the rows is unspecified (never an access out of bounds).
+ *                mixllm_build_feature_perm validates a host copy of the list.
  * 8-bit rows: s = fp16(absmax/127) per channel (or per group), q = clamp(rne(w/s),-127,127).
  * 4-bit rows, per group of 128: mn = min(w,0), mx = max(w,0), s = fp16((mx-mn)/15),
  * z = clamp(rne(-mn/s),0,15), q = clamp(rne(w/s)+z,0,15).  A scale that comes out 0 is
  * stored as 1.  All in fp32 with true division and round-half-to-even.
  * Writes packed_w8, packed_w4, scales8, scales4, zeros4, feature_perm (all device).
- * SYNCHRONIZES: feature_perm is built on the host and copied with a blocking copy before
- * the kernels are enqueued on `stream`.
+ * feature_perm is built on the device from the list (the listed channels ascending, then the
+ * others ascending); everything is enqueued on `stream`, nothing crosses to the host.
  */
-int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *salient_idx_host,
+int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *salient_idx,
                             void *packed_w8, void *packed_w4, void *scales8, void *scales4,
                             void *zeros4, int32_t *feature_perm, void *stream);
 
 /*
- * Canonical <-> packed conversion, so that callers (and tests) can inject codes produced
+ * Canonical <-> packed conversion (the ahead-of-time layout prepacking of Sec. 3.3, last
+ * paragraph, and its inverse), so that callers (and tests) can inject codes produced
  * elsewhere and read the library's codes back.  Canonical device arrays:
  *   q8 int8 [n8][K]; s8 fp16 [n8][K/w8_group]; q4 uint8 [n4][K] one code (0..15) per byte;
  *   s4 fp16 [n4][K/128]; z4 uint8 [n4][K/128] one zero point (0..15) per byte;
@@ -216,11 +234,12 @@ int mixllm_channel_salience(const mixllm_desc *d, const void *W, const void *G, 
  *   salience        device, fp32 [layer_offsets[L]]: the layers' saliences one after another;
  *                   every value finite and >= 0
  *   layer_offsets   HOST, int64 [L + 1], ascending from 0: layer l owns [offsets[l], offsets[l+1]);
- *                   read before the call returns
+ *                   read before the call returns (the values travel as kernel arguments: no copy,
+ *                   no wait)
  *   T               0 <= T <= layer_offsets[L] < 2^31
  *   selected        device, int32 [T]: the chosen channels as indices INSIDE their layer, layer after
  *                   layer, ascending inside a layer - layer l's slice is what mixllm_quantize_weights
- *                   takes as salient_idx (after a copy to the host)
+ *                   takes as salient_idx, where it lies
  *   layer_counts    device, int32 [L]: length of every layer's slice (the layer's n8)
  *   workspace       device, at least mixllm_select_salient_workspace(L) bytes, 16-byte aligned
  * Errors: EINVAL, EWORKSPACE, EHIP.
@@ -253,13 +272,32 @@ int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream);
 int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan);
 
 /*
- * Test hook: the exact int32 partial sum of every (token, channel, group), produced by the
- * integer pipeline of the chosen path (same loads, unpacking and MFMA sequence as the
- * linear), written in ORIGINAL channel order:  P int32 [M][N][K/128].
+ * Test hook: the exact int32 partial sum of every (token, channel, group) (Sec. 3.3: the MMA of the
+ * two-step dequantization, before the float step), written in ORIGINAL channel order:
+ * P int32 [M][N][K/128].  Decode paths, the path for a few dozen tokens and the tiled path run the
+ * body of the linear's own kernel with the rescale replaced by a store: the same hand-issued loads
+ * and waits, the same unpacking and MFMA sequence.  Two differences from the linear remain, both in
+ * the tiled path: no scales are passed, so the group metadata request is one load instead of two;
+ * and 8-bit tiles with one scale per channel, which the linear accumulates over all of K in one
+ * int32 (no per-group value exists there), take the per-group pipeline of the group-wise 8-bit
+ * scales.  mixllm_debug_channel_sums covers that accumulator.
  */
 int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const void *packed_w4,
                                 const void *packed_w8, const void *zeros4,
                                 const int32_t *feature_perm, int32_t *P, int path, void *stream);
+
+/*
+ * Test hook: S[m][n] = sum over the groups of P[m][n][g], int32 [M][N] in ORIGINAL channel order,
+ * from the kernels the linear itself launches for `d` (same arguments, same block shape, same loads,
+ * waits, unpacking and MFMAs; only the float rescale of a group partial is replaced by an integer
+ * add, and the epilogue stores the integer).  For 8-bit tiles with one scale per channel this is the
+ * very accumulator the linear converts and scales (Sec. 3.3 step 2 applied once per channel).
+ * path: MIXLLM_PATH_GENERIC, MIXLLM_PATH_PREFILL and its block-shape variants; others EUNSUPPORTED.
+ */
+int mixllm_debug_channel_sums(const mixllm_desc *d, const int8_t *xq, const void *xscale,
+                              const void *packed_w4, const void *packed_w8, const void *scales4,
+                              const void *scales8, const void *zeros4, const int32_t *feature_perm,
+                              int32_t *S, int path, void *stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ GROUP = 128
 
 PATH_AUTO, PATH_GENERIC, PATH_DECODE, PATH_PREFILL = 0, 1, 2, 3
 PATH_DECODE_STREAM, PATH_DECODE_RESIDENT, PATH_DECODE_SPLIT, PATH_MID = 4, 5, 6, 7
+PATH_PREFILL_32, PATH_PREFILL_64, PATH_PREFILL_128 = 8, 9, 10
 
 
 class MixllmError(RuntimeError):
@@ -61,6 +62,7 @@ def lib():
         L.mixllm_mixed_linear.argtypes = [C.POINTER(_Desc)] + [_VP] * 10 + [C.c_size_t, _VP]
         L.mixllm_mixed_linear_path.argtypes = [C.POINTER(_Desc)] + [_VP] * 10 + [C.c_size_t, C.c_int, _VP]
         L.mixllm_debug_group_partials.argtypes = [C.POINTER(_Desc)] + [_VP] * 6 + [C.c_int, _VP]
+        L.mixllm_debug_channel_sums.argtypes = [C.POINTER(_Desc)] + [_VP] * 9 + [C.c_int, _VP]
         L.mixllm_mixed_linear_fp16.argtypes = [C.POINTER(_Desc)] + [_VP] * 9 + [C.c_size_t, _VP]
         L.mixllm_channel_salience.argtypes = [C.POINTER(_Desc), _VP, _VP, C.c_float, C.c_int, _VP, _VP]
         L.mixllm_select_salient_workspace.argtypes = [C.c_int32]
@@ -75,7 +77,7 @@ def lib():
         for name in ("mixllm_query_sizes", "mixllm_build_feature_perm", "mixllm_quantize_weights",
                      "mixllm_pack_weights", "mixllm_unpack_weights", "mixllm_quantize_activations",
                      "mixllm_mixed_linear", "mixllm_mixed_linear_path", "mixllm_debug_group_partials",
-                     "mixllm_mixed_linear_fp16"):
+                     "mixllm_mixed_linear_fp16", "mixllm_debug_channel_sums"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -155,15 +157,21 @@ def _alloc_layer(K, N, n8, w8_group, device) -> PackedLayer:
 
 
 def quantize_weights(W: torch.Tensor, salient_idx, w8_group=None) -> PackedLayer:
-    """Offline: fp16 W [N,K] on the device + host list of 8-bit channels -> packed layer."""
+    """Offline: fp16 W [N,K] on the device + the list of 8-bit channels -> packed layer.  The list is
+    an int32 device tensor (say a slice of select_salient's result: nothing crosses to the host), or a
+    host sequence / numpy array, which is checked (range, duplicates) and copied to the device here."""
     assert W.dtype == torch.float16 and W.dim() == 2
     N, K = W.shape
-    sal = np.ascontiguousarray(salient_idx, dtype=np.int32)
-    L = _alloc_layer(K, N, sal.size, w8_group, W.device)
+    if isinstance(salient_idx, torch.Tensor):
+        sal = salient_idx.to(device=W.device, dtype=torch.int32).contiguous()
+    else:
+        host = np.ascontiguousarray(salient_idx, dtype=np.int32)
+        build_feature_perm(N, host)          # raises on an index out of range or a duplicate
+        sal = torch.from_numpy(host).to(W.device)
+    L = _alloc_layer(K, N, int(sal.numel()), w8_group, W.device)
     d = L.desc()
-    _check(lib().mixllm_quantize_weights(C.byref(d), _ptr(W), sal.ctypes.data if sal.size else None,
-                                         _ptr(L.w8), _ptr(L.w4), _ptr(L.s8), _ptr(L.s4), _ptr(L.z4),
-                                         _ptr(L.perm), _stream()), "mixllm_quantize_weights")
+    _check(lib().mixllm_quantize_weights(C.byref(d), _ptr(W), _ptr(sal), _ptr(L.w8), _ptr(L.w4), _ptr(L.s8),
+                                         _ptr(L.s4), _ptr(L.z4), _ptr(L.perm), _stream()), "mixllm_quantize_weights")
     return L
 
 
@@ -239,6 +247,18 @@ def debug_group_partials(xq: torch.Tensor, L: PackedLayer, path: int = PATH_AUTO
                                              _ptr(L.perm), _ptr(P), path, _stream()),
            "mixllm_debug_group_partials")
     return P
+
+
+def debug_channel_sums(xq: torch.Tensor, xs: torch.Tensor, L: PackedLayer, path: int = PATH_PREFILL) -> torch.Tensor:
+    """S [M,N] int32 = the per-group partial sums added up over the groups, from the kernels the
+    linear launches for this shape (generic or tiled path)."""
+    M, K = xq.shape
+    S = torch.empty((M, L.N), dtype=torch.int32, device=xq.device)
+    d = L.desc(M, K // xs.shape[1])
+    _check(lib().mixllm_debug_channel_sums(C.byref(d), _ptr(xq), _ptr(xs), _ptr(L.w4), _ptr(L.w8), _ptr(L.s4),
+                                           _ptr(L.s8), _ptr(L.z4), _ptr(L.perm), _ptr(S), path, _stream()),
+           "mixllm_debug_channel_sums")
+    return S
 
 
 def linear(x: torch.Tensor, L: PackedLayer, act_group=None, path: int = PATH_AUTO) -> torch.Tensor:

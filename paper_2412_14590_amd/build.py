@@ -17,7 +17,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-fhip-fp32-correctly-rounded-divide-sqrt", "-ffp-contract=off",
          # no compiler-generated packed fp32 arithmetic
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-I", INCLUDE, "-I", CSRC] + os.environ.get("MIXLLM_EXTRA_FLAGS", "").split()
+         # (the direct-to-LDS load names m0, a register the compiler reserves, among its clobbers)
+         "-Wall", "-Wno-unused-function", "-Wno-inline-asm", "-I", INCLUDE, "-I", CSRC] + os.environ.get("MIXLLM_EXTRA_FLAGS", "").split()
 
 
 def _hipcc():
@@ -27,14 +28,14 @@ def _hipcc():
 
 
 # sources with hand-issued loads -> the kernels in them that must not spill
-NO_SPILL = {"linear_prefill.hip": lambda n: "linear_prefill_kernel" in n and re.search(r"EEELi\dELb0ELb[01]ELb[01]EEEv", n) is not None,
+NO_SPILL = {"linear_prefill.hip": lambda n: "linear_prefill_kernel" in n,
             "linear_decode_split.hip": lambda n: "linear_decode_split_kernel" in n,
             "linear_mid.hip": lambda n: "linear_mid_kernel" in n}
 
 
 def _check_no_scratch(src: str, compile_log: str) -> None:
-    """Kernels that issue their loads by hand (every prefill variant with template flag DUMP=0,
-    every evenly split decode kernel, every kernel for a few dozen tokens) must not spill: a register saved to
+    """Kernels that issue their loads by hand (every tiled kernel, every evenly split decode kernel,
+    every kernel for a few dozen tokens, the debug variants included) must not spill: a register saved to
     scratch between such a load and its wait would be saved before the data has arrived.  Their
     sources are compiled with -Rpass-analysis=kernel-resource-usage; fail the build if one of
     those kernels reports scratch."""
@@ -62,7 +63,12 @@ def check_hand_issued_loads(asm_text: str, name: str) -> None:
     load written in inline asm and the next inline-asm `s_waitcnt vmcnt`, no instruction of the
     compiler's may read or write the load's destination registers - the data is not there yet.
     (This is what happens when a hand-loaded variable is reinterpreted through memory: the compiler
-    keeps it in pieces, splits the register right after the load and reassembles it for the wait.)"""
+    keeps it in pieces, splits the register right after the load and reassembles it for the wait.)
+    Limits of the scan: it judges straight-line code only.  The set of pending registers is dropped
+    at every label and branch, so a load issued before a loop's back edge and awaited after it is
+    not followed around the edge; the kernels are written so that every wait that ties a register
+    (await_loads / await_slot / tie_slot) sits in the same unrolled body as the first use, and the
+    no-spill check above covers the other way a register could be touched early."""
     pending, in_asm, bad = {}, False, []
     for i, line in enumerate(asm_text.split("\n"), 1):
         t = line.strip()

@@ -24,7 +24,8 @@ int check_desc(const mixllm_desc *d)
     if (d->group != G || d->K % G != 0) return MIXLLM_EUNSUPPORTED;
     if (d->act_group != d->K && d->act_group != G) return MIXLLM_EUNSUPPORTED;
     if (d->w8_group != d->K && d->w8_group != G) return MIXLLM_EUNSUPPORTED;
-    if (d->K > (1 << 20) || d->N > (1 << 24) || d->M > (1 << 24)) return MIXLLM_EUNSUPPORTED;
+    // K: an 8-bit channel with one scale keeps ONE int32 sum over all of K (K * 127 * 127 < 2^31)
+    if (d->K > MIXLLM_MAX_K || d->N > (1 << 24) || d->M > (1 << 24)) return MIXLLM_EUNSUPPORTED;
     return MIXLLM_OK;
 }
 
@@ -71,6 +72,7 @@ LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xsc
     p.z4 = (const uint8_t *)z4;
     p.perm = perm;
     p.variant = DECODE_ANY;
+    p.prefill_tm = 0;
     return p;
 }
 
@@ -122,34 +124,55 @@ namespace {
 
 int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 
-int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t st)
+// Which kernel a call takes: the caller's path argument with AUTO resolved, or a negative status
+// when that path does not cover the shape.  Host arithmetic only; nothing is launched, so that a
+// call can refuse before it has enqueued anything.  `q` receives the parameters the launch uses.
+int resolve_path(const mixllm_desc &d, const LinearParams &p, int path, LinearParams &q)
 {
+    q = p;
     if (path == MIXLLM_PATH_AUTO)
         path = d.M <= 16 ? MIXLLM_PATH_DECODE : (d.M <= 64 && mid_covers(p)) ? MIXLLM_PATH_MID : MIXLLM_PATH_PREFILL;
+    const bool sums = p.S != nullptr;   // the sums over the groups come from the generic and the tiled kernel only
     switch (path) {
     case MIXLLM_PATH_GENERIC:
-        if (d.M > 65535) return MIXLLM_EUNSUPPORTED;
-        return hip_status(launch_linear_generic(p, st));
+        return d.M > 65535 ? MIXLLM_EUNSUPPORTED : path;
     case MIXLLM_PATH_DECODE:
-        if (d.M > 16) return MIXLLM_EUNSUPPORTED;
-        return hip_status(launch_linear_decode(p, st));
+        return (d.M > 16 || sums) ? MIXLLM_EUNSUPPORTED : path;
     case MIXLLM_PATH_DECODE_STREAM:
     case MIXLLM_PATH_DECODE_RESIDENT:
-    case MIXLLM_PATH_DECODE_SPLIT: {
-        if (d.M > 16) return MIXLLM_EUNSUPPORTED;
-        LinearParams q = p;
+    case MIXLLM_PATH_DECODE_SPLIT:
+        if (d.M > 16 || sums) return MIXLLM_EUNSUPPORTED;
         q.variant = path == MIXLLM_PATH_DECODE_STREAM ? DECODE_STREAM : path == MIXLLM_PATH_DECODE_RESIDENT ? DECODE_RESIDENT : DECODE_SPLIT;
         if (path == MIXLLM_PATH_DECODE_SPLIT && !decode_split_covers(q)) return MIXLLM_EUNSUPPORTED;
-        return hip_status(launch_linear_decode(q, st));
-    }
+        return path;
     case MIXLLM_PATH_MID:
-        if (!mid_covers(p)) return MIXLLM_EUNSUPPORTED;
-        return hip_status(launch_linear_mid(p, st));
+        return (!mid_covers(p) || sums) ? MIXLLM_EUNSUPPORTED : path;
     case MIXLLM_PATH_PREFILL:
-        return hip_status(launch_linear_prefill(p, st));
+    case MIXLLM_PATH_PREFILL_32:
+    case MIXLLM_PATH_PREFILL_64:
+    case MIXLLM_PATH_PREFILL_128:
+        q.prefill_tm = path == MIXLLM_PATH_PREFILL_32 ? 1 : path == MIXLLM_PATH_PREFILL_64 ? 2 : path == MIXLLM_PATH_PREFILL_128 ? 4 : 0;
+        return prefill_covers(q) ? MIXLLM_PATH_PREFILL : MIXLLM_EUNSUPPORTED;
     default:
         return MIXLLM_EINVAL;
     }
+}
+
+int run_path(const LinearParams &q, int path, hipStream_t st)
+{
+    switch (path) {
+    case MIXLLM_PATH_GENERIC: return hip_status(launch_linear_generic(q, st));
+    case MIXLLM_PATH_MID: return hip_status(launch_linear_mid(q, st));
+    case MIXLLM_PATH_PREFILL: return hip_status(launch_linear_prefill(q, st));
+    default: return hip_status(launch_linear_decode(q, st));   // MIXLLM_PATH_DECODE and its variants
+    }
+}
+
+int dispatch(const mixllm_desc &d, const LinearParams &p, int path, hipStream_t st)
+{
+    LinearParams q;
+    const int r = resolve_path(d, p, path, q);
+    return r < 0 ? r : run_path(q, r, st);
 }
 
 }  // namespace
@@ -168,7 +191,7 @@ const char *mixllm_status_string(int status)
     }
 }
 
-int mixllm_abi_version(void) { return 1; }
+int mixllm_abi_version(void) { return 2; }
 
 int mixllm_query_sizes(const mixllm_desc *d, mixllm_sizes *out)
 {
@@ -192,7 +215,7 @@ int mixllm_build_feature_perm(int32_t N, int32_t n8, const int32_t *salient_idx_
     return MIXLLM_OK;
 }
 
-int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *salient_idx_host,
+int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *salient_idx,
                             void *packed_w8, void *packed_w4, void *scales8, void *scales4, void *zeros4,
                             int32_t *feature_perm, void *stream)
 {
@@ -200,15 +223,14 @@ int mixllm_quantize_weights(const mixllm_desc *d, const void *W, const int32_t *
     mixllm_sizes s;
     sizes_of(*d, s);
     if (!W || !aligned16(W) || !feature_perm || !aligned16(feature_perm)) return MIXLLM_EINVAL;
+    if (d->n8 > 0 && (!salient_idx || ((uintptr_t)salient_idx & 3u))) return MIXLLM_EINVAL;
     if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(scales8, s.scales8_bytes) ||
         !buf_ok(scales4, s.scales4_bytes) || !buf_ok(zeros4, s.zeros4_bytes))
         return MIXLLM_EINVAL;
-    std::vector<int32_t> perm((size_t)d->N);
-    if (int rc = mixllm_build_feature_perm(d->N, d->n8, salient_idx_host, perm.data())) return rc;
-    if (hipMemcpy(feature_perm, perm.data(), s.perm_bytes, hipMemcpyHostToDevice) != hipSuccess)
-        return MIXLLM_EHIP;
-    return hip_status(launch_quantize_weights(*d, W, packed_w8, packed_w4, scales8, scales4, zeros4,
-                                              feature_perm, (hipStream_t)stream));
+    // the order of the rows is built on the device, from the device list: nothing crosses to the host
+    hipStream_t st = (hipStream_t)stream;
+    if (int rc = hip_status(launch_build_feature_perm(d->N, d->n8, salient_idx, feature_perm, st))) return rc;
+    return hip_status(launch_quantize_weights(*d, W, packed_w8, packed_w4, scales8, scales4, zeros4, feature_perm, st));
 }
 
 int mixllm_pack_weights(const mixllm_desc *d, const int8_t *q8, const void *s8, const uint8_t *q4,
@@ -265,25 +287,28 @@ int mixllm_quantize_activations(const mixllm_desc *d, const void *x, int8_t *xq,
     return hip_status(launch_quantize_activations(*d, x, xq, xscale, (hipStream_t)stream));
 }
 
+// Exactly one of y (the linear), P (per-group partial sums) and S (their sums over the groups) is given.
 static int linear_common(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
                          const void *packed_w8, const void *scales4, const void *scales8,
-                         const void *zeros4, const int32_t *feature_perm, void *y, int32_t *P, int path,
-                         void *stream)
+                         const void *zeros4, const int32_t *feature_perm, void *y, int32_t *P, int32_t *S,
+                         int path, void *stream)
 {
     if (int rc = check_desc(d)) return rc;
-    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_MID) return MIXLLM_EINVAL;
+    if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_PREFILL_128) return MIXLLM_EINVAL;
     if (d->M == 0) return MIXLLM_OK;
     mixllm_sizes s;
     sizes_of(*d, s);
     if (!xq || !aligned16(xq) || !feature_perm || !aligned16(feature_perm)) return MIXLLM_EINVAL;
-    if (!P && (!xscale || !aligned16(xscale) || !y || !aligned16(y))) return MIXLLM_EINVAL;
-    if (P && !aligned16(P)) return MIXLLM_EINVAL;
+    if (!P && (!xscale || !aligned16(xscale))) return MIXLLM_EINVAL;
+    if (!P && !S && (!y || !aligned16(y))) return MIXLLM_EINVAL;
+    if ((P && !aligned16(P)) || (S && !aligned16(S))) return MIXLLM_EINVAL;
     if (!buf_ok(packed_w8, s.w8_bytes) || !buf_ok(packed_w4, s.w4_bytes) || !buf_ok(zeros4, s.zeros4_bytes))
         return MIXLLM_EINVAL;
     if (!P && (!buf_ok(scales8, s.scales8_bytes) || !buf_ok(scales4, s.scales4_bytes))) return MIXLLM_EINVAL;
     LinearParams p = make_params(*d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm);
     p.y = (half_t *)y;
     p.P = P;
+    p.S = S;
     return dispatch(*d, p, path, (hipStream_t)stream);
 }
 
@@ -292,10 +317,10 @@ int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void 
                              const void *scales8, const void *zeros4, const int32_t *feature_perm, void *y,
                              void *workspace, size_t workspace_bytes, int path, void *stream)
 {
-    (void)workspace;   // no path needs scratch memory: mixllm_query_sizes reports 0
+    (void)workspace;   // no kernel of the linear needs scratch memory
     (void)workspace_bytes;
     return linear_common(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, y,
-                         nullptr, path, stream);
+                         nullptr, nullptr, path, stream);
 }
 
 int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
@@ -307,10 +332,11 @@ int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xsca
                                     feature_perm, y, workspace, workspace_bytes, MIXLLM_PATH_AUTO, stream);
 }
 
-int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *packed_w4, const void *packed_w8,
-                             const void *scales4, const void *scales8, const void *zeros4,
-                             const int32_t *feature_perm, void *y, void *workspace, size_t workspace_bytes,
-                             void *stream)
+// fp16 activations in, fp16 outputs out; `scratch` (device, 16-byte aligned, scratch_bytes long) holds xq
+// and xscale between the quantizer and the linear where one kernel cannot do both.
+static int linear_from_fp16(const mixllm_desc *d, const void *x, const void *packed_w4, const void *packed_w8,
+                            const void *scales4, const void *scales8, const void *zeros4, const int32_t *feature_perm,
+                            void *y, void *scratch, size_t scratch_bytes, hipStream_t st)
 {
     if (int rc = check_desc(d)) return rc;
     if (d->M == 0) return MIXLLM_OK;
@@ -327,17 +353,32 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
     // kernel's launch and round trips (one token; a few tokens of a short row).
     if (decode_can_fuse_quantizer(p)) {
         p.x = (const half_t *)x;
-        return hip_status(launch_linear_decode(p, (hipStream_t)stream));
+        const int e = launch_linear_decode(p, st);
+        if (e != (int)hipErrorInvalidValue) return hip_status(e);
+        p.x = nullptr;   // no variant took the shape after all (nothing was launched): two kernels
     }
-    // two kernels: the stand-alone quantizer into the workspace, then the linear
-    if (!workspace || !aligned16(workspace)) return MIXLLM_EINVAL;
-    if (workspace_bytes < s.workspace_bytes) return MIXLLM_EWORKSPACE;
-    int8_t *xq = (int8_t *)workspace;
-    void *xscale = (uint8_t *)workspace + round_up_sz(s.xq_bytes, 256);
-    if (int rc = hip_status(launch_quantize_activations(*d, x, xq, xscale, (hipStream_t)stream))) return rc;
+    // two kernels: the stand-alone quantizer into the scratch area, then the linear; the kernel of the
+    // linear is chosen, and the call refused if none takes the shape, before the quantizer is enqueued
+    if (!scratch || !aligned16(scratch)) return MIXLLM_EINVAL;
+    if (scratch_bytes < s.workspace_bytes) return MIXLLM_EWORKSPACE;
+    int8_t *xq = (int8_t *)scratch;
+    void *xscale = (uint8_t *)scratch + round_up_sz(s.xq_bytes, 256);
     p.xq = xq;
     p.xscale = (const half_t *)xscale;
-    return dispatch(*d, p, MIXLLM_PATH_AUTO, (hipStream_t)stream);
+    LinearParams q;
+    const int path = resolve_path(*d, p, MIXLLM_PATH_AUTO, q);
+    if (path < 0) return path;
+    if (int rc = hip_status(launch_quantize_activations(*d, x, xq, xscale, st))) return rc;
+    return run_path(q, path, st);
+}
+
+int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *packed_w4, const void *packed_w8,
+                             const void *scales4, const void *scales8, const void *zeros4,
+                             const int32_t *feature_perm, void *y, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    return linear_from_fp16(d, x, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, y, workspace,
+                            workspace_bytes, (hipStream_t)stream);
 }
 
 int mixllm_channel_salience(const mixllm_desc *d, const void *W, const void *G, float weight, int accumulate,
@@ -398,7 +439,16 @@ int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const vo
 {
     if (!P) return MIXLLM_EINVAL;
     return linear_common(d, xq, nullptr, packed_w4, packed_w8, nullptr, nullptr, zeros4, feature_perm,
-                         nullptr, P, path, stream);
+                         nullptr, P, nullptr, path, stream);
+}
+
+int mixllm_debug_channel_sums(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
+                              const void *packed_w8, const void *scales4, const void *scales8,
+                              const void *zeros4, const int32_t *feature_perm, int32_t *S, int path, void *stream)
+{
+    if (!S) return MIXLLM_EINVAL;
+    return linear_common(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, nullptr,
+                         nullptr, S, path, stream);
 }
 
 }  // extern "C"

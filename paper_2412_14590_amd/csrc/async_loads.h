@@ -21,7 +21,7 @@ namespace mixllm {
 // 16 bytes per lane, global -> LDS: lane l writes lds_base + 16 l.  lds_base is wave uniform.
 static __device__ inline void load_lds16(uint32_t lds_base, uint32_t voff, const void *sbase)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 template <int OFF>
 static __device__ inline void load_reg16(v4i &dst, uint32_t voff, const void *sbase)

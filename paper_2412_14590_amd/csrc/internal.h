@@ -32,6 +32,7 @@ struct LinearParams {
     int act_per_token;   // 1: xscale [M], 0: xscale [M][ng]
     int w8_per_channel;  // 1: scales8 [n8p], 0: scales8 [n8p][ngp]
     int variant;         // decode variant requested by the caller's path argument (DECODE_ANY = library's choice)
+    int prefill_tm;      // token tiles of 32 per wave of the tiled kernel requested by the caller's path argument (0 = library's choice)
     const half_t *x;   // fp16 activations [M][K]: set only by the fused quantize + linear entry point
     const int8_t *xq;
     const half_t *xscale;
@@ -42,7 +43,8 @@ struct LinearParams {
     const uint8_t *z4;
     const int32_t *perm;
     half_t *y;        // linear output, or
-    int32_t *P;       // partials output (debug entry point); exactly one of y / P is used
+    int32_t *P;       // per-group partial sums [M][N][ng] (debug entry point), or
+    int32_t *S;       // their sums over the groups [M][N] (debug entry point); exactly one of y / P / S is used
 };
 
 // ---- packed-layout addressing (see mixllm.h for the layout description) ----
@@ -132,6 +134,8 @@ int launch_quantize_activations(const mixllm_desc &d, const void *x, int8_t *xq,
 int launch_check_fast_division(unsigned long long *mismatches, hipStream_t st);
 int launch_quantize_weights(const mixllm_desc &d, const void *W, void *w8, void *w4, void *s8,
                             void *s4, void *z4, const int32_t *perm, hipStream_t st);
+// feature_perm [N] from a device list of the n8 channels kept at 8 bits (quant_weights.hip)
+int launch_build_feature_perm(int N, int n8, const int32_t *salient_idx_dev, int32_t *perm, hipStream_t st);
 int launch_pack_weights(const mixllm_desc &d, const int8_t *q8, const void *s8c, const uint8_t *q4,
                         const void *s4c, const uint8_t *z4c, void *w8, void *w4, void *s8,
                         void *s4, void *z4, hipStream_t st);
@@ -152,6 +156,7 @@ int cu_count();
 // true when launch_linear_decode can take fp16 activations (p.x) and quantize them itself
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);
+bool prefill_covers(const LinearParams &p);
 bool prefill_plan(const LinearParams &p, int out[8]);
 // path for 17..128 tokens (linear_mid.hip)
 bool mid_covers(const LinearParams &p);

@@ -608,7 +608,7 @@ static int launch_resident(const LinearParams &p, int nblk8, int per8, int nblk4
 template <int WPB>
 static int try_launch_resident(const LinearParams &p, int blocks_per_cu, hipStream_t st)
 {
-    const int slots = 256 * blocks_per_cu;   // blocks resident at once
+    const int slots = cu_count() * blocks_per_cu;   // blocks resident at once
     auto blocks = [&](int i4) {
         const int i8 = i4 >= 2 ? i4 / 2 : 1;
         return (p.ntiles4 + i4 - 1) / i4 + (p.ntiles8 + i8 - 1) / i8;
@@ -675,7 +675,7 @@ int launch_linear_decode(const LinearParams &p, hipStream_t st)
     const int nquads = (p.ng + 3) / 4;
     const int tpw = (tiles >= 300 && p.M > 4) ? 2 : 1;
     int wpb = 1;
-    while (wpb < 8 && wpb * 2 <= nquads && tiles * wpb * 2 <= 2048) wpb *= 2;
+    while (wpb < 8 && wpb * 2 <= nquads && tiles * wpb * 2 <= 8 * cu_count()) wpb *= 2;
     return tpw == 2 ? launch_wpb<2>(p, wpb, st) : launch_wpb<1>(p, wpb, st);
 }
 

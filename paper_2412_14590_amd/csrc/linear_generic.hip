@@ -16,7 +16,8 @@ static __device__ inline int dot4(uint32_t a, uint32_t b, int acc)
     return acc;
 }
 
-template <bool DUMP>
+// DUMP: 0 = the linear, 1 = the per-group partial sums, 2 = their integer sums over the groups
+template <int DUMP>
 __global__ __launch_bounds__(256) void linear_generic_kernel(LinearParams p)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;   // row of the concatenation [8-bit ; 4-bit]
@@ -26,6 +27,7 @@ __global__ __launch_bounds__(256) void linear_generic_kernel(LinearParams p)
     const int8_t *xrow = p.xq + (size_t)m * p.K;
     const int nsteps = p.K / 64;
     float acc = 0.0f;
+    int isum = 0;
     for (int g = 0; g < p.ng; ++g) {
         int P = 0;
         float sw = 0.0f;
@@ -42,7 +44,7 @@ __global__ __launch_bounds__(256) void linear_generic_kernel(LinearParams p)
                     P = dot4(a.z, w.z, P);
                     P = dot4(a.w, w.w, P);
                 }
-            if (!DUMP) sw = (float)(p.w8_per_channel ? p.s8[r] : p.s8[(size_t)r * p.ngp + g]);
+            if (DUMP == 0) sw = (float)(p.w8_per_channel ? p.s8[r] : p.s8[(size_t)r * p.ngp + g]);
         } else {
             const int r = j - p.n8;
             const uint32_t zb = zbias(z4_load(p.z4, r, g, p.ngp));
@@ -61,15 +63,18 @@ __global__ __launch_bounds__(256) void linear_generic_kernel(LinearParams p)
                     P = dot4(a.w, (uint32_t)b3, P);
                 }
             }
-            if (!DUMP) sw = (float)p.s4[(size_t)r * p.ngp + g];
+            if (DUMP == 0) sw = (float)p.s4[(size_t)r * p.ngp + g];
         }
-        if (DUMP) {
+        if (DUMP == 1) {
             p.P[((size_t)m * p.N + c) * p.ng + g] = P;
+        } else if (DUMP == 2) {
+            isum += P;
         } else {
             const float sa = (float)(p.act_per_token ? p.xscale[m] : p.xscale[(size_t)m * p.ng + g]);
             acc += (float)P * sw * sa;
         }
     }
+    if (DUMP == 2) p.S[(size_t)m * p.N + c] = isum;
     if (!DUMP) p.y[(size_t)m * p.N + c] = (half_t)acc;
 }
 
@@ -78,9 +83,11 @@ int launch_linear_generic(const LinearParams &p, hipStream_t st)
     if (p.M == 0 || p.N == 0) return hipSuccess;
     dim3 grid((p.N + 255) / 256, p.M);
     if (p.P)
-        hipLaunchKernelGGL(linear_generic_kernel<true>, grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL(linear_generic_kernel<1>, grid, dim3(256), 0, st, p);
+    else if (p.S)
+        hipLaunchKernelGGL(linear_generic_kernel<2>, grid, dim3(256), 0, st, p);
     else
-        hipLaunchKernelGGL(linear_generic_kernel<false>, grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL(linear_generic_kernel<0>, grid, dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 

@@ -74,7 +74,11 @@ struct Shape {
 // instantiated with ASYNC use no scratch memory.)  Without ASYNC they are ordinary loads, which
 // the compiler awaits itself - later than necessary, because it does not see the hand-issued
 // activation loads ahead of them in the queue, but always correctly.
-template <typename C, bool DUMP, bool ACT_PT, bool PART8, bool PG8, bool ASYNC>
+// DUMP: 0 = the linear; 1 = debug entry point, the int32 partial of every (token, channel, group)
+// leaves the loop instead of being rescaled (no scales are passed, none are loaded); 2 = debug
+// entry point, the partials are added up in int32 over the groups instead of being rescaled:
+// same arguments, loads, waits, unpack and MFMAs as the linear.
+template <typename C, int DUMP, bool ACT_PT, bool PART8, bool PG8, bool ASYNC>
 static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a, float *lds_sa)
 {
     constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG, RING = C::RING;
@@ -85,7 +89,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     constexpr int PPS = 8 / (NSLOT - HALF);  // eighths of the next group's unpack per slot of the second half
     static_assert(PPS * (NSLOT - HALF) == 8, "the unpack is spread evenly over the second half of the group");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+    const int wm = C::WM == 1 ? 0 : wave / WN, wn = wave % WN;
     const int n32 = lane & 31, h = lane >> 5;
     const int ntiles = PART8 ? p.ntiles8 : p.ntiles4;
     const int nrows = PART8 ? p.n8 : p.n4;
@@ -133,7 +137,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // packed 4-bit weights are requested WD groups before the wait for them (hand-issued loads
     // only: with ordinary loads the wait below cannot count what is younger in the queue)
     constexpr int WD = ASYNC ? C::WD : 1, NRAW = 2 * WD;
-    constexpr int NMETA = 2;   // load instructions of load_meta in the hand-issued variant
+    constexpr int NMETA = DUMP == 1 ? 1 : 2;   // load instructions load_meta issues for a 4-bit tile in the hand-issued variant
     v4i raw[NRAW][2];
     auto load_b = [&](int g, auto setc) {
         constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW;
@@ -172,16 +176,16 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         const int g0 = 4 * min(q, (ng - 1) / 4);
         if (ASYNC) {
             if (PART8) {
-                if (!DUMP && per_group_s8) load_reg8(mt.s, s_voff, p.s8 + g0);
+                if (DUMP != 1 && per_group_s8) load_reg8(mt.s, s_voff, p.s8 + g0);
             } else {
-                if (!DUMP) load_reg8(mt.s, s_voff, p.s4 + g0);
+                if (DUMP != 1) load_reg8(mt.s, s_voff, p.s4 + g0);
                 load_reg_u16(mt.z, z_voff, p.z4 + g0 / 2);
             }
         } else {
             if (PART8) {
-                if (!DUMP && per_group_s8) mt.s = *(const uint2 *)((const uint8_t *)(p.s8 + g0) + s_voff);
+                if (DUMP != 1 && per_group_s8) mt.s = *(const uint2 *)((const uint8_t *)(p.s8 + g0) + s_voff);
             } else {
-                if (!DUMP) mt.s = *(const uint2 *)((const uint8_t *)(p.s4 + g0) + s_voff);
+                if (DUMP != 1) mt.s = *(const uint2 *)((const uint8_t *)(p.s4 + g0) + s_voff);
                 mt.z = *(const uint16_t *)(p.z4 + g0 / 2 + z_voff);
             }
         }
@@ -191,11 +195,16 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         return half_bits_to_float((u & 1) ? d >> 16 : d & 0xffffu);
     };
     // one eighth of the unpack of a group: raw dword d of `set` -> two operand dwords
-    auto unpack_piece = [&](auto setc, auto dc, uint32_t zb) {
+    // (`keep`, DUMP == 2 only: all bits set, or zero for a group past the end of K, whose weights
+    // then unpack to zeros - together with a zero point of zero - where the linear multiplies the
+    // group's partial by a zero scale)
+    auto unpack_piece = [&](auto setc, auto dc, uint32_t zb, uint32_t keep) {
         constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW, d = decltype(dc)::value;
         constexpr int bj = d >> 1, e = d & 1;
         int lo, hi;
-        unpack_sub((uint32_t)raw[rset][bj & 1][(bj >> 1) * 2 + e], zb, lo, hi);
+        uint32_t w = (uint32_t)raw[rset][bj & 1][(bj >> 1) * 2 + e];
+        if (DUMP == 2) w &= keep;
+        unpack_sub(w, zb, lo, hi);
         b[set][bj][2 * e] = lo;
         b[set][bj][2 * e + 1] = hi;
     };
@@ -205,23 +214,35 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     for (int i = 0; i < 16; ++i) zero16[i] = 0;
 
     float acc[TM][16];
+    int isum[TM][16];   // DUMP == 2: the partials added up as integers
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) {
+            acc[mt][r] = 0.0f;
+            isum[mt][r] = 0;
+        }
 
     // Rescale (or, for the debug entry point, dump) registers 4j..4j+3 of one finished tile:
     // rows m0 + mw0 + 32 mt + 8 j + 4 h + {0..3}, column = this lane's channel.
-    auto finish4 = [&](const v16i &P, auto mtc, auto jc, float sw, int gp) {
+    // `opaque0` (DUMP == 1) is a zero the compiler cannot see through: with it the store addresses
+    // are computed where they are used instead of all 16 TM of them being kept in registers across
+    // the K loop.
+    auto finish4 = [&](const v16i &P, auto mtc, auto jc, float sw, int gp, int opaque0) {
         constexpr int mt = decltype(mtc)::value, j = decltype(jc)::value;
-        if (DUMP) {
+        if (DUMP == 1) {
             if (gp >= 0 && gp < ng && ch >= 0) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int m = m0 + mw0 + mt * 32 + 8 * j + 4 * h + i;
+                    const int m = m0 + mw0 + mt * 32 + 8 * j + 4 * h + i + opaque0;
                     if (m < p.M) p.P[((size_t)m * p.N + ch) * ng + gp] = P[4 * j + i];
                 }
             }
+        } else if (DUMP == 2) {
+            // (a group past the end of K, which the linear multiplies by a zero scale, has had its
+            // weights replaced by zeros: see group_step)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) isum[mt][4 * j + i] += P[4 * j + i];
         } else if (ACT_PT) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[mt][4 * j + i] = __builtin_fmaf((float)P[4 * j + i], sw, acc[mt][4 * j + i]);
@@ -252,7 +273,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     uint32_t sa_bits = 0;
     const uint32_t sa_voff = (uint32_t)min(m0 + min(tid, BM - 1), p.M - 1) * (uint32_t)ng * 2u;
     const uint32_t lds_sa_thread = lds_address(lds_sa) + (uint32_t)min(tid, BM - 1) * (uint32_t)sizeof(float);   // this thread's cell of stage 0
-    if (!ACT_PT && !DUMP) {
+    if (!ACT_PT && DUMP != 1) {
         if (tid < BM) {
 #pragma unroll
             for (int s = 1; s < NSTAGE; ++s) lds_sa[s * BM + tid] = 0.0f;   // read (times a zero scale) before first written
@@ -260,7 +281,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         }
         load_reg_u16(sa_bits, sa_voff, p.xscale + min(1, ng - 1));
     }
-    const float sw_row = (PART8 && !DUMP && !PG8) ? (float)p.s8[rw] : 0.0f;
+    const float sw_row = (PART8 && DUMP != 1 && !PG8) ? (float)p.s8[rw] : 0.0f;
     // everything above has landed (registers and LDS)
     await_loads<0>(meta_cur.s, meta_cur.z);
     await_loads<0>(sa_bits);
@@ -270,7 +291,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     meta_nxt = meta_cur;
     if (!PART8) {
         const uint32_t zb = zbias(meta_cur.z & 15);
-        static_for<0, 8>([&](auto dc) { unpack_piece(std::integral_constant<int, 0>{}, dc, zb); });
+        static_for<0, 8>([&](auto dc) { unpack_piece(std::integral_constant<int, 0>{}, dc, zb, 0xffffffffu); });
     }
     v4i af[RING];
     // fragment of slot t of the group held in `stage`
@@ -295,13 +316,20 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         float sw_cur;
         if (PART8 && !per_group_s8) sw_cur = g < ng ? sw_row : 0.0f;
         else sw_cur = scale_of(meta_cur, U);   // zero for groups past the end (padding)
+        int opaque0 = 0;
+        if (DUMP == 1) asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
         uint32_t zb_next = 0;
+        const uint32_t keep_next = g + 1 < ng ? 0xffffffffu : 0u;
         // 8-bit weights need no unpack: group g+1 is requested here, straight into the operand
         // registers group g-1 just vacated; this group's own request (one group old, only the
         // previous middle's activation loads are younger) has to have landed
         if (PART8) {
             await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
             load_b(g + 1, std::integral_constant<int, U + 1>{});
+            if (DUMP == 2 && g >= ng) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[U % 2][j] = v4i{0, 0, 0, 0};
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -331,7 +359,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 if (PART8) await_loads<YOUNGER>();
                 else await_loads<YOUNGER>(raw[(U + 1) % NRAW][0], raw[(U + 1) % NRAW][1]);
                 if constexpr (U == 3) await_loads<YOUNGER>(meta_nxt.s, meta_nxt.z);
-                if (!ACT_PT && !DUMP) {
+                if (!ACT_PT && DUMP != 1) {
                     await_loads<YOUNGER>(sa_bits);
                     // every thread stores (threads past the tile repeat its last row's value): no
                     // branch in the middle of the group, and a store the compiler does not have to
@@ -339,12 +367,13 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                     const float sa_val = half_bits_to_float(sa_bits);
                     asm volatile("ds_write_b32 %0, %1" ::"v"(lds_sa_thread + (uint32_t)(((U + 1) % NSTAGE) * BM * sizeof(float))), "v"(sa_val) : "memory");
                 }
-                mid_group_barrier<(!ACT_PT && !DUMP)>();
+                mid_group_barrier<(!ACT_PT && DUMP != 1)>();
                 if constexpr (U == 1) load_meta(g / 4 + 1, meta_nxt);
-                if (!ACT_PT && !DUMP) load_reg_u16(sa_bits, sa_voff, p.xscale + min(g + 2, ng - 1));
+                if (!ACT_PT && DUMP != 1) load_reg_u16(sa_bits, sa_voff, p.xscale + min(g + 2, ng - 1));
                 if (!PART8) load_b(g + 1 + WD, std::integral_constant<int, U + 1 + WD>{});
                 load_a(g + 3, (U + 3) % NSTAGE);
                 if (!PART8) zb_next = zbias(((U == 3 ? meta_nxt.z : meta_cur.z) >> (4 * ((U + 1) % 4))) & 15);
+                if (!PART8 && DUMP == 2 && !keep_next) zb_next = 0x80808080u;
                 __builtin_amdgcn_sched_barrier(0);
             }
             // request the fragment DFRAG slots ahead (second half: from the next group's stage)
@@ -354,14 +383,14 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 load_frag(std::integral_constant<int, (U + 1) % NSTAGE>{}, std::integral_constant<int, st + DFRAG - NSLOT>{});
             P[s][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][j], j == 0 ? zero16 : P[s][i], 0, 0, 0);
             finish4(P[s ^ 1][i], std::integral_constant<int, up>{}, std::integral_constant<int, j>{},
-                    q == 0 ? sw_prev : sw_cur, gp);
+                    q == 0 ? sw_prev : sw_cur, gp, opaque0);
             if constexpr (!PART8 && st >= HALF) {
                 static_for<0, PPS>([&](auto ec) {
                     unpack_piece(std::integral_constant<int, U + 1>{},
-                                 std::integral_constant<int, PPS * (st - HALF) + decltype(ec)::value>{}, zb_next);
+                                 std::integral_constant<int, PPS * (st - HALF) + decltype(ec)::value>{}, zb_next, keep_next);
                 });
             }
-            if (!DUMP) {
+            if (DUMP != 1) {
                 // issue order: MFMA, the LDS read(s), the vector instructions in its shadow
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, ACT_PT ? 1 : 2, 0);
@@ -383,7 +412,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     static_for<0, SB>([&](auto tc) {
         constexpr int t = decltype(tc)::value, j = t / NB, i = t % NB, qp = NBG - 1;
         constexpr int s_last = (3 * NBG + qp) & 1;   // accumulator set of the last bundle of a group with g & 3 == 3
-        finish4(P[s_last][i], std::integral_constant<int, NB * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last);
+        finish4(P[s_last][i], std::integral_constant<int, NB * qp + i>{}, std::integral_constant<int, j>{}, sw_prev, g_last, 0);
     });
     // Drain: the last requests (clamped re-reads past the end of K) are still in flight, aimed at
     // this block's LDS and at registers nothing reads any more.  Tying those registers to the
@@ -394,7 +423,21 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
     await_loads<0>(meta_nxt.s, meta_nxt.z);
     await_loads<0>(sa_bits);
-    if (DUMP) return;
+    if (DUMP == 1) return;
+    if (DUMP == 2) {
+        // (the channel passes through an empty asm statement so that no store address is computed,
+        // and kept in registers, before the K loop)
+        int ch_out = ch;
+        asm volatile("" : "+v"(ch_out));
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < p.M && ch_out >= 0) p.S[(size_t)m * p.N + ch_out] = isum[mt][r];
+            }
+        return;
+    }
 
     // ---- epilogue: token scale, fp16, scatter (Sec. 3.4) ------------------------------
     // per token tile: the 16 token scales of the lane's rows are fetched together (clamped,
@@ -421,7 +464,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
 // over all of K in int32 (|sum| <= K * 127 * 127 < 2^31 for K < 133000) and are converted and
 // scaled once at the end.  Same activation pipeline as prefill_block; the four token tiles are
 // four independent accumulation chains issued round robin.
-template <typename C, bool ACT_PT>
+template <typename C, bool ACT_PT, int DUMP>
 static __device__ inline void prefill_block_w8_channel_scale(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a,
                                                             float *lds_sa)
 {
@@ -470,6 +513,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     load_a(1, 1);
     load_a(2, 2);
     static_assert(ACT_PT, "an integer sum over groups needs an activation scale that does not depend on the group");
+    static_assert(DUMP != 1, "one accumulator over all of K: there is no per-group partial to dump");
     const float sw_row = (float)p.s8[rw];
     await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
     __syncthreads();
@@ -539,12 +583,14 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            if (m < p.M && ch >= 0) p.y[(size_t)m * p.N + ch] = (half_t)((float)P[mt][r] * sw_row * sa[r]);
+            if (DUMP == 2) {
+                if (m < p.M && ch >= 0) p.S[(size_t)m * p.N + ch] = P[mt][r];
+            } else if (m < p.M && ch >= 0) p.y[(size_t)m * p.N + ch] = (half_t)((float)P[mt][r] * sw_row * sa[r]);
         }
     }
 }
 
-template <typename C, int MINW, bool DUMP, bool ACT_PT, bool W8PC>
+template <typename C, int MINW, int DUMP, bool ACT_PT, bool W8PC>
 __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm, int nb8,
                                                                          int nb4, int per4, int per8, int band)
 {
@@ -571,10 +617,10 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
     const int r = L - bd * band * nb;
     const int bn = r / w, bm = bd * band + r % w;
     constexpr int T16 = C::BN / TILE_N;
-    constexpr bool ASYNC = !DUMP;   // every variant but the debug dump issues its loads by hand; spill free (checked by the build)
+    constexpr bool ASYNC = true;   // every variant issues its loads by hand; spill free (checked by the build)
     if (part8) {
-        if constexpr (W8PC && ACT_PT && !DUMP)
-            prefill_block_w8_channel_scale<C, ACT_PT>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+        if constexpr (W8PC && ACT_PT && DUMP != 1)
+            prefill_block_w8_channel_scale<C, ACT_PT, DUMP>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
         else
             prefill_block<C, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
     } else
@@ -636,19 +682,28 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
     const PrefillGrid gr = grid_of(p, C::BM, C::BN);
     const int nbm = gr.nbm, nb8 = gr.nb8, nb4 = gr.nb4, per4 = gr.per4, per8 = gr.per8, band = gr.band;
     dim3 grid((per4 + per8) * 8), block(C::THREADS);
-    if (p.P)
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, true, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+    auto go = [&](auto kernel, bool with_sa) {
+        return launch_variant<C>(kernel, with_sa, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+    };
+    // per-group partials (debug entry point): every tile through the per-group pipeline
+    if (p.P) return go(linear_prefill_kernel<C, MINW, 1, true, false>, false);
+    // the linear, or (debug entry point) the same kernels adding the partials up as integers
     if (p.act_per_token && p.w8_per_channel)
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, true>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
-    if (p.act_per_token)
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, true, false>, false, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+        return p.S ? go(linear_prefill_kernel<C, MINW, 2, true, true>, false) : go(linear_prefill_kernel<C, MINW, 0, true, true>, false);
+    if (p.act_per_token) {
+        if (!p.S) return go(linear_prefill_kernel<C, MINW, 0, true, false>, false);
+        // the sums with group-wise 8-bit scales: built for one and two token tiles per wave (with four the
+        // 8-bit tiles of this variant do not fit the register file)
+        if constexpr (C::TM <= 2) return go(linear_prefill_kernel<C, MINW, 2, true, false>, false);
+        return (int)hipErrorInvalidValue;
+    }
     // Per-(token, group) activation scales: built for one and two token tiles per wave.  With four
     // the kernel needs more than 256 registers (the scale reads from LDS and the extra multiply
     // come on top of 235), and a kernel with hand-issued loads must not spill.
     if constexpr (C::TM <= 2) {
         if (p.w8_per_channel)
-            return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, true>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
-        return launch_variant<C>(linear_prefill_kernel<C, MINW, false, false, false>, true, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+            return p.S ? go(linear_prefill_kernel<C, MINW, 2, false, true>, true) : go(linear_prefill_kernel<C, MINW, 0, false, true>, true);
+        return p.S ? go(linear_prefill_kernel<C, MINW, 2, false, false>, true) : go(linear_prefill_kernel<C, MINW, 0, false, false>, true);
     }
     return (int)hipErrorInvalidValue;
 }
@@ -656,21 +711,32 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
 // token tiles (of 32) per wave: 4 = blocks of 128 x 128, 2 = 64 x 128, 1 = 32 x 128
 static int token_tiles_per_wave(const LinearParams &p)
 {
+    // variants only built for one and two token tiles per wave: group-wise activation scales; the debug
+    // sums with group-wise 8-bit scales
+    const bool group_scaled_acts = (!p.act_per_token && !p.P) || (p.S && !p.w8_per_channel);
+    if (p.prefill_tm) return (p.prefill_tm == 4 && group_scaled_acts) ? 0 : p.prefill_tm;   // the caller's choice (tests, benchmarks)
     const long nbn = (p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
     const long tiles128 = (long)((p.M + 127) / 128) * nbn, tiles64 = (long)((p.M + 63) / 64) * nbn;
     if (3 * tiles64 <= 2 * cu_count()) return 1;
-    if (3 * tiles128 <= 2 * cu_count() || (!p.act_per_token && !p.P)) return 2;
+    if (3 * tiles128 <= 2 * cu_count() || group_scaled_acts) return 2;
     return 4;
+}
+
+// Shapes the kernel takes: lanes address activations, packed weights and metadata with 32-bit byte
+// offsets; a caller-chosen block shape must exist for the scale granularity.
+bool prefill_covers(const LinearParams &p)
+{
+    const size_t lim = (size_t)1 << 31;
+    if ((size_t)p.M * (size_t)p.K >= lim || (size_t)p.ntiles4 * TILE_N * (size_t)p.K / 2 >= lim ||
+        (size_t)p.ntiles8 * TILE_N * (size_t)p.K >= lim)
+        return false;
+    return p.M >= 1 && p.N >= 1 && token_tiles_per_wave(p) != 0;
 }
 
 int launch_linear_prefill(const LinearParams &p, hipStream_t st)
 {
     if (p.M == 0 || p.N == 0) return hipSuccess;
-    // lanes address activations, packed weights and metadata with 32-bit byte offsets
-    const size_t lim = (size_t)1 << 31;
-    if ((size_t)p.M * (size_t)p.K >= lim || (size_t)p.ntiles4 * TILE_N * (size_t)p.K / 2 >= lim ||
-        (size_t)p.ntiles8 * TILE_N * (size_t)p.K >= lim)
-        return (int)hipErrorInvalidValue;
+    if (!prefill_covers(p)) return (int)hipErrorInvalidValue;
     // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower).
     // Where that grid has clearly less than one block per CU the chip is short of waves, not of rate:
     // blocks of 64 x 128 (wave tile 64 x 32) or 32 x 128 (wave tile 32 x 32) double the waves and
@@ -692,7 +758,7 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
 // the host-side test of the block -> tile mapping
 bool prefill_plan(const LinearParams &p, int out[8])
 {
-    if (p.M < 1 || p.N < 1) return false;
+    if (!prefill_covers(p)) return false;
     const int tm = token_tiles_per_wave(p);
     const int BM = 32 * tm, BN = 128;
     const PrefillGrid g = grid_of(p, BM, BN);
@@ -703,7 +769,7 @@ bool prefill_plan(const LinearParams &p, int out[8])
     out[4] = g.nb4;
     out[5] = (g.per4 + g.per8) * 8;
     out[6] = g.band;
-    out[7] = NSTAGE * BM * G + ((!p.act_per_token && !p.P) ? NSTAGE * BM * (int)sizeof(float) : 16);
+    out[7] = NSTAGE * BM * G + ((!p.act_per_token && !p.P) ? NSTAGE * BM * (int)sizeof(float) : 16);   // (p.P is never set here)
     return true;
 }
 

@@ -20,6 +20,80 @@ static __device__ inline float block_max_256(float v, float *red)
     return v;
 }
 
+// ------------------------------------------------- order of the concatenated rows --
+// feature_perm from a DEVICE list of the 8-bit channels (Sec. 3.4: the two parts own different
+// channel indices; Alg. 1's per-layer slice arrives on the device from mixllm_select_salient):
+// the listed channels ascending, then all others ascending.  No scratch memory: while the order
+// is being built, bit 31 of perm[c] says "channel c is in the list" and the low 31 bits are the
+// entry under construction (channel numbers are below 2^24).
+
+__global__ __launch_bounds__(256) void perm_clear_kernel(int32_t *__restrict__ perm, int N)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < N) perm[c] = 0;
+}
+
+// An index outside [0, N) is ignored; a channel listed twice is marked once.
+__global__ __launch_bounds__(256) void perm_mark_kernel(const int32_t *__restrict__ idx, int n8, int32_t *__restrict__ perm,
+                                                        int N)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n8) {
+        const int c = idx[i];
+        if (c >= 0 && c < N) perm[c] = (int32_t)0x80000000u;
+    }
+}
+
+// One block walks the channels in order, 1024 at a time: a marked channel goes to the next free
+// position of the first part, an unmarked one to the next free position of the second part.
+// Position and channel of a write differ, so a write keeps the mark bit of the word it lands in
+// (only the thread that owns a position writes its low bits; the mark bit is only ever read).
+// With fewer than n8 distinct valid indices in the list the second part would run past N: those
+// writes are dropped (the call's contract is a list of n8 distinct channels; a bad list gives an
+// unspecified order, never an access out of bounds).
+__global__ __launch_bounds__(1024) void perm_scan_kernel(int32_t *__restrict__ perm, int N, int n8)
+{
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int marked_before = 0;   // marked channels in the chunks already walked
+    for (int c0 = 0; c0 < N; c0 += 1024) {
+        const int c = c0 + tid;
+        const int flag = (c < N && perm[c] < 0) ? 1 : 0;
+        int inc = flag;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += t;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();   // every flag of the chunk has been read; wave totals are visible
+        int base = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) base += wave_tot[w];
+            total += wave_tot[w];
+        }
+        const int a = marked_before + base + inc - flag;   // marked channels before c
+        if (c < N) {
+            const int pos = flag ? a : n8 + (c - a);
+            if (pos < N) perm[pos] = (perm[pos] & (int32_t)0x80000000u) | c;
+        }
+        marked_before += total;
+        __syncthreads();   // wave_tot is rewritten by the next chunk; this chunk's writes are done
+    }
+    for (int c = tid; c < N; c += 1024) perm[c] &= 0x7fffffff;
+}
+
+int launch_build_feature_perm(int N, int n8, const int32_t *salient_idx_dev, int32_t *perm, hipStream_t st)
+{
+    if (N <= 0) return (int)hipSuccess;
+    hipLaunchKernelGGL(perm_clear_kernel, dim3((N + 255) / 256), dim3(256), 0, st, perm, N);
+    if (n8 > 0)
+        hipLaunchKernelGGL(perm_mark_kernel, dim3((n8 + 255) / 256), dim3(256), 0, st, salient_idx_dev, n8, perm, N);
+    hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, st, perm, N, n8);
+    return (int)hipGetLastError();
+}
+
 // ------------------------------------------------------------------ quantize + pack --
 
 // blocks [0, n8p): one 8-bit row each; blocks [n8p, n8p + n4p): one 4-bit row each.

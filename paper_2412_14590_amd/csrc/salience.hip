@@ -210,6 +210,17 @@ __global__ __launch_bounds__(256) void select_emit_kernel(const uint32_t *__rest
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// The layer offsets come from a host array that may be gone when the call returns, and the call
+// must neither block nor stage a copy: they travel as kernel arguments, 128 at a time.
+struct OffsetChunk {
+    int64_t v[128];
+};
+__global__ void select_offsets_kernel(int64_t *dst, int n, OffsetChunk c)
+{
+    const int t = threadIdx.x;
+    if (t < n) dst[t] = c.v[t];
+}
+
 }  // namespace
 
 int launch_channel_salience(const void *W, const void *Gr, int N, int K, float weight, int accumulate, float *salience,
@@ -239,9 +250,12 @@ int launch_select_salient(const float *salience, const int64_t *layer_offsets_ho
     uint32_t *gt = (uint32_t *)ws, *eq = (uint32_t *)(ws + per), *eq_take = (uint32_t *)(ws + 2 * per),
              *out_off = (uint32_t *)(ws + 3 * per);
     const int64_t total = layer_offsets_host[L];
-    // the host array may be gone when the call returns: a synchronous copy
-    hipError_t e = hipMemcpy(offsets, layer_offsets_host, sizeof(int64_t) * (size_t)(L + 1), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return (int)e;
+    for (int o = 0; o <= L; o += 128) {
+        OffsetChunk c;
+        const int n = std::min(128, L + 1 - o);
+        for (int i = 0; i < 128; ++i) c.v[i] = i < n ? layer_offsets_host[o + i] : 0;
+        hipLaunchKernelGGL(select_offsets_kernel, dim3(1), dim3(128), 0, st, offsets + o, n, c);
+    }
     const uint32_t *keys = (const uint32_t *)salience;
     hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(256), 0, st, state, (uint32_t)T);
     const int blocks = (int)std::min<int64_t>(2048, (total + 255) / 256);

@@ -1,6 +1,8 @@
 """GPU parity: every entry point of the C-ABI library against the CPU oracle on the same
-seeded inputs.  Integer results (codes, zero points, permutations, per-group partial sums)
-must be bit-exact; fp16 outputs must agree within TOL (row-L2-normalised)."""
+seeded inputs.  Integer results (codes, zero points, permutations, per-group partial sums and
+their sums over the groups) must be bit-exact; fp16 outputs must agree within TOL
+(row-L2-normalised, the workload's gate) and, element by element, within half an fp16 unit in the
+last place plus the fp32 accumulation bound (util.elementwise_bound)."""
 import numpy as np
 import pytest
 import torch
@@ -9,13 +11,16 @@ import paper_2412_14590_amd as mx
 from oracle import ref
 from paper_2412_14590_amd import synth
 
-from util import G, TOL, dev, make_case, pack_from_oracle, row_rel_err
+from util import (G, TOL, check_against_oracle, dev, full_size_layer, make_case, pack_from_oracle, row_rel_err,
+                  stratified_rows)
 
 pytestmark = pytest.mark.gpu
 
 PATHS = {"generic": mx.PATH_GENERIC, "decode": mx.PATH_DECODE, "prefill": mx.PATH_PREFILL,
          "decode_stream": mx.PATH_DECODE_STREAM, "decode_resident": mx.PATH_DECODE_RESIDENT,
-         "decode_split": mx.PATH_DECODE_SPLIT, "mid": mx.PATH_MID}
+         "decode_split": mx.PATH_DECODE_SPLIT, "mid": mx.PATH_MID,
+         "prefill32": mx.PATH_PREFILL_32, "prefill64": mx.PATH_PREFILL_64, "prefill128": mx.PATH_PREFILL_128}
+TILED = ["prefill", "prefill32", "prefill64", "prefill128"]   # the tiled kernel: block shape by grid size, or forced
 DECODE_VARIANTS = ["decode_stream", "decode_resident", "decode_split"]
 
 
@@ -143,6 +148,38 @@ def test_quantizers_on_random_shapes_and_value_ranges():
         assert np.array_equal(xq.cpu().numpy(), xq_ref), (M, K, ag, scale)
 
 
+@pytest.mark.parametrize("N,n8", [(1, 0), (1, 1), (16, 5), (1000, 0), (1000, 1000), (1025, 100), (4096, 410), (57344, 5734),
+                                  (3000, 2999)])
+def test_feature_perm_is_built_on_the_device_from_a_device_list(N, n8):
+    # mixllm_quantize_weights takes the list of 8-bit channels as a device pointer, in any order
+    rng = np.random.default_rng(N + n8)
+    sal = rng.permutation(N)[:n8].astype(np.int32)
+    W = synth.make_w(N, 128, seed=5, n_outlier_rows=1)
+    PL = mx.quantize_weights(dev(W), dev(sal))
+    assert np.array_equal(PL.perm.cpu().numpy(), ref.feature_perm(N, sal))
+
+
+def test_a_bad_device_list_of_8bit_channels_never_writes_out_of_bounds():
+    # indices out of range are ignored, duplicates count once; the order is then unspecified, but
+    # every entry stays a channel number and the buffers around feature_perm are untouched
+    N, K = 200, 128
+    W = dev(synth.make_w(N, K, seed=6, n_outlier_rows=1))
+    sal = dev(np.array([5, 5, -1, 7, 4000, 199, 7, 2 ** 30], np.int32))
+    guard = torch.full((N + 64,), -77, dtype=torch.int32, device="cuda")
+    L = mx.binding._alloc_layer(K, N, 8, None, W.device)
+    L.perm = guard[32:32 + N]
+    d = L.desc()
+    import ctypes as C
+    rc = mx.lib().mixllm_quantize_weights(C.byref(d), W.data_ptr(), sal.data_ptr(), L.w8.data_ptr(), L.w4.data_ptr(),
+                                          L.s8.data_ptr(), L.s4.data_ptr(), L.z4.data_ptr(), L.perm.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert rc == 0
+    g = guard.cpu().numpy()
+    assert (g[:32] == -77).all() and (g[32 + N:] == -77).all()
+    assert ((g[32:32 + N] >= 0) & (g[32:32 + N] < N)).all()
+    assert list(g[32:36]) == [5, 7, 199, 0]      # the three valid distinct channels first; the other slots of the first part stay cleared
+
+
 # ------------------------------------------------------------ integer partial sums --
 
 def check_partials(M, K, N, n8, path, seed=24):
@@ -167,10 +204,33 @@ def test_group_partials_bit_exact_small_m(M, K, N, n8, path):
                                      # grids that take the 64 x 128 and the 128 x 128 blocks (the smaller cases
                                      # above run on 32 x 128 blocks), K not a multiple of 4 groups
                                      (256, 384, 8192, 819), (384, 640, 8192, 0)])
-@pytest.mark.parametrize("path", ["generic", "prefill"])
+@pytest.mark.parametrize("path", ["generic"] + TILED)
 def test_group_partials_bit_exact_tiled(M, K, N, n8, path):
+    # every block shape of the tiled kernel (the shape only decides which tokens share a block)
     say("partials", path, M, K, N, n8)
     check_partials(M, K, N, n8, path)
+
+
+@pytest.mark.parametrize("variant", ["baseline", "paper", "w8_grouped"])
+@pytest.mark.parametrize("M,K,N,n8", [(3, 256, 7, 2), (130, 512, 300, 30), (200, 1024, 530, 0), (33, 384, 70, 70),
+                                     (257, 256, 290, 29), (256, 384, 8192, 819), (384, 640, 8192, 0), (300, 4096, 272, 272)])
+def test_channel_sums_from_the_linears_own_kernels(M, K, N, n8, variant):
+    # Sum over the groups of the int32 partials, out of the kernels the linear launches for the shape and
+    # scale granularity: for 8-bit tiles with one scale per channel this is the single accumulator
+    # that runs over all of K.  Bit-exact against the oracle's partials, through every block shape.
+    ag, wg = {"baseline": (None, None), "paper": (128, 128), "w8_grouped": (None, 128)}[variant]
+    _, _, L, _, xq, xs = make_case(M, K, N, n8, seed=33, w8_group=wg, act_group=ag)
+    S_ref = ref.group_partials(xq, L).sum(axis=2, dtype=np.int64)
+    assert np.abs(S_ref).max() < 2 ** 31
+    PL = pack_from_oracle(L)
+    for name in ["generic"] + TILED:
+        try:
+            S = mx.debug_channel_sums(dev(xq), dev(xs), PL, PATHS[name])
+        except mx.MixllmError as e:
+            # 128 x 128 blocks are not built for group-wise activation scales, nor (the sums only) for group-wise 8-bit scales
+            assert e.status == -2 and name == "prefill128" and variant != "baseline", (name, variant)
+            continue
+        assert np.array_equal(S.cpu().numpy().astype(np.int64), S_ref), (name, variant, M, K, N, n8)
 
 
 def test_group_partials_worst_case_magnitudes():
@@ -203,12 +263,10 @@ def test_group_partials_worst_case_magnitudes():
 def check_linear(M, K, N, n8, path, variant="baseline", seed=25):
     act_group, w8_group = (None, None) if variant == "baseline" else (128, 128)
     _, _, L, _, xq, xs = make_case(M, K, N, n8, seed, w8_group, act_group)
-    y_ref = ref.mixed_linear(xq, xs, L)
     y = mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), PATHS[path])
     torch.cuda.synchronize()
-    err = row_rel_err(y.cpu().numpy(), y_ref)
-    say(f"  linear {path} {variant} M={M} K={K} N={N} n8={n8}: row rel err {err:.2e}")
-    assert err <= TOL
+    _, err = check_against_oracle(y.cpu().numpy(), xq, xs, L, (path, variant, M, K, N, n8))
+    say(f"  linear {path} {variant} M={M} K={K} N={N} n8={n8}: row rel err {err:.2e}, every element within its bound")
 
 
 @pytest.mark.parametrize("variant", ["baseline", "paper"])
@@ -222,10 +280,16 @@ def test_linear_small_m(M, K, N, n8, path, variant):
 
 
 @pytest.mark.parametrize("variant", ["baseline", "paper"])
-@pytest.mark.parametrize("path", ["generic", "prefill"])
+@pytest.mark.parametrize("path", ["generic"] + TILED)
 @pytest.mark.parametrize("M,K,N,n8", [(17, 256, 7, 2), (130, 512, 300, 30), (200, 1024, 530, 0), (33, 384, 70, 70),
                                      (512, 4096, 1024, 102), (256, 384, 8192, 819), (384, 640, 8192, 0)])
 def test_linear_tiled(M, K, N, n8, path, variant):
+    if path == "prefill128" and variant == "paper":
+        _, _, L, _, xq, xs = make_case(M, K, N, n8, 25, 128, 128)
+        with pytest.raises(mx.MixllmError) as e:     # not built: refused, no other shape taken silently
+            mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), PATHS[path])
+        assert e.value.status == -2
+        return
     check_linear(M, K, N, n8, path, variant)
 
 
@@ -387,97 +451,118 @@ def test_random_shapes_through_every_path_that_covers_them():
     say("  60 random shapes: all paths agree with the oracle")
 
 
+def tiled_shape_of(M, lay):
+    """The forced-shape path equal to the block shape the tiled kernel picks for this layer at M tokens."""
+    import ctypes as C
+    from paper_2412_14590_amd import binding
+    out = (C.c_int32 * 8)()
+    d = binding._desc(M, lay.K, lay.N, lay.n8)
+    assert mx.lib().mixllm_debug_work_split(C.byref(d), mx.PATH_PREFILL, C.cast(out, C.c_void_p)) == 0
+    return {32: mx.PATH_PREFILL_32, 64: mx.PATH_PREFILL_64, 128: mx.PATH_PREFILL_128}[out[0]]
+
+
+def check_cell(lay, L, PL, M, seed, act_group=None):
+    """One (layer, M) cell of a workload at full size, through the call the benchmark times
+    (mixllm_mixed_linear_fp16, library's choice of kernel).
+    Up to 64 tokens: every row against the oracle (row norm and per element), codes, scales and the
+    per-group partials of the dispatched kernel bit-exact.
+    More tokens (the oracle is O(MNK)): a stratified sample of rows against the oracle the same way
+    (one row per 32-token tile, first and last row of every 128-token block), and ALL rows against
+    the one-thread-per-output kernel on the GPU, which the sample pins to the oracle: the int32 sums
+    over the groups out of the timed kernels bit-exact, the fp16 outputs within two roundings."""
+    tag = (lay.name, lay.K, lay.N, lay.n8, M, act_group)
+    x = synth.make_x(M, lay.K, seed=seed + M)
+    xd = dev(x)
+    y = mx.linear_fp16(xd, PL, act_group=act_group)
+    rows = np.arange(M) if M <= 64 else stratified_rows(M, seed + M)
+    xq_ref, xs_ref = ref.quantize_act(x[rows], act_group)
+    P_ref, err = check_against_oracle(y.cpu().numpy()[rows], xq_ref, xs_ref, L, tag)
+    xq, xs = mx.quantize_activations(xd, act_group)
+    assert np.array_equal(xq.cpu().numpy()[rows], xq_ref), tag
+    assert np.array_equal(xs.cpu().numpy()[rows].view(np.uint16), xs_ref.view(np.uint16)), tag
+    if M <= 64:
+        P = mx.debug_group_partials(xq, PL)
+        assert np.array_equal(P.cpu().numpy(), P_ref), tag
+        say(f"  {lay.name} K={lay.K} N={lay.N} n8={lay.n8} M={M}: all rows, row rel err {err:.2e}, elements within bound, partials exact")
+        return
+    S = mx.debug_channel_sums(xq, xs, PL, mx.PATH_PREFILL)
+    Sg = mx.debug_channel_sums(xq, xs, PL, mx.PATH_GENERIC)
+    assert torch.equal(S, Sg), tag
+    assert np.array_equal(Sg.cpu().numpy()[rows].astype(np.int64), P_ref.sum(axis=2, dtype=np.int64)), tag
+    del S, Sg
+    yg = mx.mixed_linear(xq, xs, PL, mx.PATH_GENERIC).float()
+    yt = mx.mixed_linear(xq, xs, PL).float()
+    assert torch.equal(yt.half(), y), tag        # the fp16 entry point is quantizer + this launch
+    rms = yg.pow(2).mean(dim=1, keepdim=True).sqrt()
+    # both kernels round the same fp32-accurate value to fp16: one unit in the last place apart at
+    # most, plus their accumulation errors (a few 1e-5 of the row's typical magnitude)
+    assert bool(((yt - yg).abs() <= yg.abs() * 2.0 ** -10 + 2e-4 * rms + 1e-7).all()), tag
+    say(f"  {lay.name} K={lay.K} N={lay.N} n8={lay.n8} M={M}: {len(rows)} sampled rows row rel err {err:.2e}, elements within "
+        f"bound; all rows: integer sums exact, outputs agree with the generic kernel")
+
+
+def check_block_partials(lay, L, PL, M, rows, seed):
+    """Per-group int32 partials out of the tiled kernel in the block shape it uses for this layer at
+    M tokens (hand-issued loads and all), on a contiguous run of token rows, against the oracle."""
+    x = synth.make_x(M, lay.K, seed=seed + M)[rows]
+    xq_ref, _ = ref.quantize_act(x)
+    P = mx.debug_group_partials(dev(xq_ref), PL, tiled_shape_of(M, lay))
+    assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref, L)), (lay.name, M)
+    say(f"  {lay.name} K={lay.K} N={lay.N}: partials of {len(rows)} rows exact in the block shape used at M={M}")
+
+
 @pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
 def test_llama3_8b_decode_layers_full_size(name):
-    K, N = synth.LLAMA3_8B[name]
-    lay = synth.make_layer(name, K, N, seed=1)
-    say("8B decode", name, K, N, lay.n8)
-    L = ref.quantize_weights(lay.W, lay.salient_idx)
-    PL = mx.quantize_weights(dev(lay.W), lay.salient_idx)
+    # workload 2: every layer of the block at M in {1, 4, 8, 16}, every row
+    lay, L, PL = full_size_layer("8b", name)
+    say("8B decode", name, lay.K, lay.N, lay.n8)
     u = mx.unpack_weights(PL)
     assert np.array_equal(u["q4"].cpu().numpy(), L.q4) and np.array_equal(u["q8"].cpu().numpy(), L.q8)
     assert np.array_equal(u["z4"].cpu().numpy(), L.z4)
+    assert np.array_equal(u["s4"].cpu().numpy().view(np.uint16), L.s4.view(np.uint16))
+    assert np.array_equal(u["s8"].cpu().numpy().view(np.uint16), L.s8.view(np.uint16))
     for M in (1, 4, 8, 16):
-        x = synth.make_x(M, K, seed=100 + M)
-        xq_ref, xs_ref = ref.quantize_act(x)
-        xq, xs = mx.quantize_activations(dev(x))
-        assert np.array_equal(xq.cpu().numpy(), xq_ref)
-        y = mx.mixed_linear(xq, xs, PL)
-        y_ref = ref.mixed_linear(xq_ref, xs_ref, L)
-        err = row_rel_err(y.cpu().numpy(), y_ref)
-        say(f"  M={M}: row rel err {err:.2e}")
-        assert err <= TOL
-        if M == 16:
-            P = mx.debug_group_partials(xq, PL, mx.PATH_DECODE)
-            assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref, L))
+        check_cell(lay, L, PL, M, seed=100)
 
 
-@pytest.mark.parametrize("name,M", [("o", 2048), ("qkv", 512), ("gate_up", 2048), ("down", 2048)])
-def test_llama3_8b_prefill_layers_full_size_sampled_rows(name, M):
-    # The GPU runs the whole layer in the configuration the benchmark times; the O(MNK)
-    # oracle checks a seeded sample of token rows (all N channels, all groups).
-    K, N = synth.LLAMA3_8B[name]
-    lay = synth.make_layer(name, K, N, seed=1)
-    say("8B prefill", name, M, K, N)
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+def test_llama3_8b_prefill_layers_full_size(name):
+    # workload 3: every layer at M in {512, 2048, 8192}, in the configuration the benchmark times
+    lay, L, PL = full_size_layer("8b", name)
+    say("8B prefill", name, lay.K, lay.N, lay.n8)
+    for M in (512, 2048, 8192):
+        check_cell(lay, L, PL, M, seed=200)
+    # per-group partials out of the 128 x 128 block shape (the one timed at M = 2048): a whole block
+    # of 128 tokens, and a ragged one
+    check_block_partials(lay, L, PL, 2048, np.arange(128, 256), seed=200)
+    check_block_partials(lay, L, PL, 2048, np.arange(2000, 2048), seed=200)
+
+
+@pytest.mark.parametrize("name", ["qkv", "o", "gate_up", "down"])
+def test_llama31_70b_layers(name):
+    # workload 4: the Llama-3.1-70B-shaped layers (N(0, 0.015) weights, N/64 outlier rows), M sweep
+    lay, L, PL = full_size_layer("70b", name, seed=2)
+    say("70B", name, lay.K, lay.N, lay.n8)
+    for M in (1, 16, 64, 256, 2048):
+        check_cell(lay, L, PL, M, seed=300)
+    check_block_partials(lay, L, PL, 2048, np.arange(1024, 1024 + (128 if name in ("qkv", "o") else 40)), seed=300)
+
+
+def test_paper_granularity_full_size_layers():
+    # the paper's scale granularity (activation scales per token and group, 8-bit weight scales per
+    # group; Sec. 3.1.2, Sec. 4.1) on two full-size layers, decode and tiled path
+    for name in ("o", "down"):
+        lay, L, PL = full_size_layer("8b", name, w8_group=128)
+        for M in (1, 16, 512, 2048):
+            check_cell(lay, L, PL, M, seed=700, act_group=128)
+
+
+def _check_layer(lay, Ms, seed):
+    """A layer drawn for one test (8-bit share sweeps): oracle and GPU quantization, then the cells."""
     L = ref.quantize_weights(lay.W, lay.salient_idx)
     PL = mx.quantize_weights(dev(lay.W), lay.salient_idx)
-    x = synth.make_x(M, K, seed=200)
-    xq, xs = mx.quantize_activations(dev(x))
-    y = mx.mixed_linear(xq, xs, PL)
-    rows = np.sort(np.random.default_rng(7).choice(M, 24, replace=False))
-    rows[0], rows[-1] = 0, M - 1
-    xq_ref, xs_ref = ref.quantize_act(x[rows])
-    assert np.array_equal(xq.cpu().numpy()[rows], xq_ref)
-    y_ref = ref.mixed_linear(xq_ref, xs_ref, L)
-    err = row_rel_err(y.cpu().numpy()[rows], y_ref)
-    say(f"  row rel err {err:.2e}")
-    assert err <= TOL
-    # integer pipeline of the tiled path at full N and K on those rows
-    P = mx.debug_group_partials(dev(xq_ref), PL, mx.PATH_PREFILL)
-    assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref, L))
-
-
-def _check_layer(lay, Ms_full, Ms_sampled, seed, partial_rows=8):
-    """One full-size layer against the oracle: every row for small M, a seeded sample of token rows
-    (all channels, all groups) for large M; integer partials of the dispatched path on a few rows."""
-    L = ref.quantize_weights(lay.W, lay.salient_idx)
-    PL = mx.quantize_weights(dev(lay.W), lay.salient_idx)
-    for M in Ms_full:
-        x = synth.make_x(M, lay.K, seed=seed + M)
-        xq_ref, xs_ref = ref.quantize_act(x)
-        y = mx.linear_fp16(dev(x), PL)
-        err = row_rel_err(y.cpu().numpy(), ref.mixed_linear(xq_ref, xs_ref, L))
-        say(f"  {lay.name} K={lay.K} N={lay.N} n8={lay.n8} M={M}: row rel err {err:.2e}")
-        assert err <= TOL
-    for M in Ms_sampled:
-        x = synth.make_x(M, lay.K, seed=seed + M)
-        y = mx.linear_fp16(dev(x), PL)
-        rows = np.sort(np.random.default_rng(seed).choice(M, min(M, 16), replace=False))
-        rows[0], rows[-1] = 0, M - 1
-        xq_ref, xs_ref = ref.quantize_act(x[rows])
-        err = row_rel_err(y.cpu().numpy()[rows], ref.mixed_linear(xq_ref, xs_ref, L))
-        say(f"  {lay.name} K={lay.K} N={lay.N} n8={lay.n8} M={M} (sampled rows): row rel err {err:.2e}")
-        assert err <= TOL
-        xs_small = dev(xq_ref[:partial_rows])
-        for path in (mx.PATH_DECODE, mx.PATH_PREFILL):
-            P = mx.debug_group_partials(xs_small, PL, path)
-            assert np.array_equal(P.cpu().numpy(), ref.group_partials(xq_ref[:partial_rows], L))
-
-
-@pytest.mark.parametrize("name,Ms_full,Ms_sampled", [("qkv", (1, 16), (64, 256)), ("o", (1, 16), (256, 2048)),
-                                                    ("gate_up", (1,), (64,)), ("down", (1, 16), (256,))])
-def test_llama31_70b_layers(name, Ms_full, Ms_sampled):
-    # the Llama-3.1-70B-shaped layers of the workload list: N(0, 0.015) weights, N/64 outlier rows
-    K, N = synth.LLAMA31_70B[name]
-    lay = synth.make_layer(name, K, N, sigma=synth.SIGMA["70b"], n_outlier_rows=N // 64, seed=2)
-    say("70B", name, K, N, lay.n8)
-    _check_layer(lay, Ms_full, Ms_sampled, seed=300)
-
-
-def test_llama3_8b_prefill_8192_tokens_sampled_rows():
-    K, N = synth.LLAMA3_8B["o"]
-    lay = synth.make_layer("o", K, N, seed=1)
-    _check_layer(lay, (), (8192,), seed=400)
+    for M in Ms:
+        check_cell(lay, L, PL, M, seed)
 
 
 @pytest.mark.parametrize("N", [4096, 14336])
@@ -489,7 +574,7 @@ def test_single_linear_8bit_share_sweep(N, share):
     K = 4096
     lay = synth.make_layer(f"sweep{N}", K, N, frac8=share, seed=77)
     say(f"share sweep: N={N} share={share} n8={lay.n8}")
-    _check_layer(lay, (1, 16), (1024,), seed=600 + int(100 * share), partial_rows=4)
+    _check_layer(lay, (1, 16, 1024), seed=600 + int(100 * share))
 
 
 def test_uneven_8bit_share_across_a_32_layer_stack():
@@ -514,7 +599,7 @@ def test_uneven_8bit_share_across_a_32_layer_stack():
         lay = synth.make_layer(name, K, N, frac8=f, seed=1000 + layer)
         say(f"uneven: layer {layer} {name} share {f:.3f} n8={lay.n8}")
         assert lay.n8 == synth.n8_for(N, f)
-        _check_layer(lay, (1,), (256,), seed=500 + layer, partial_rows=4)
+        _check_layer(lay, (1, 256), seed=500 + layer)
 
 
 # ------------------------------------------------- global precision search (Sec. 3.2) --
@@ -592,12 +677,13 @@ def test_precision_search_end_to_end_feeds_the_linear():
     want = ref.select_salient([s.cpu().numpy() for s in sal], T)     # same fp32 saliences: same decision
     assert sum(len(c) for c in chosen) == T
     for (K, N), W, idx, idx_ref in zip(shapes, Ws, chosen, want):
-        idx = idx.cpu().numpy()
-        assert np.array_equal(idx, idx_ref)
-        L = ref.quantize_weights(W, idx)
+        # the layer's slice of the selection goes into the weight quantizer where it lies, on the
+        # device: nothing between the search and the linear crosses to the host
         PL = mx.quantize_weights(dev(W), idx)
-        x = synth.make_x(5, K, seed=70)
-        xq, xs = ref.quantize_act(x)
-        y = mx.linear(dev(x), PL)
-        assert row_rel_err(y.cpu().numpy(), ref.mixed_linear(xq, xs, L)) <= TOL
+        y = mx.linear(dev(synth.make_x(5, K, seed=70)), PL)
+        assert np.array_equal(idx.cpu().numpy(), idx_ref)
+        L = ref.quantize_weights(W, idx_ref)
+        assert np.array_equal(PL.perm.cpu().numpy(), L.perm)
+        xq, xs = ref.quantize_act(synth.make_x(5, K, seed=70))
+        check_against_oracle(y.cpu().numpy(), xq, xs, L, ("search", K, N))
     say("precision search: 8-bit channels per layer", [len(c) for c in chosen])

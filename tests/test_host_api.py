@@ -27,7 +27,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert len(names) >= 10
     for n in names:
         assert hasattr(L, n), n
-    assert mx.abi_version() >= 1
+    assert mx.abi_version() >= 2
 
 
 def test_query_sizes_matches_the_layout_arithmetic_and_paper_footprints():
@@ -57,6 +57,7 @@ def test_query_sizes_matches_the_layout_arithmetic_and_paper_footprints():
     (dict(M=-1, K=256, N=64, n8=0), -1),
     (dict(M=1, K=256, N=64, n8=0, act_group=64), -2),
     (dict(M=1, K=256, N=64, n8=0, w8_group=256 * 2), -2),
+    (dict(M=1, K=131072 + 128, N=64, n8=0), -2),    # beyond the K an int32 sum over all of K is safe for
 ])
 def test_bad_descriptors_are_rejected(kw, code):
     d = binding._desc(**kw)
@@ -71,11 +72,20 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
     assert L.mixllm_mixed_linear(C.byref(d), None, None, None, None, None, None, None, None, None, None, 0, None) == -1
     assert L.mixllm_quantize_activations(C.byref(d), None, None, None, None) == -1
     assert L.mixllm_debug_group_partials(C.byref(d), None, None, None, None, None, None, 0, None) == -1
+    assert L.mixllm_debug_channel_sums(C.byref(d), None, None, None, None, None, None, None, None, None, 0, None) == -1
     # misaligned (fake, never dereferenced: validation fails first)
     fake = 0x1000
+    # the list of 8-bit channels is a device pointer: null with n8 > 0, or not 4-byte aligned
+    assert L.mixllm_quantize_weights(C.byref(d), fake, None, fake, fake, fake, fake, fake, fake, None) == -1
+    assert L.mixllm_quantize_weights(C.byref(d), fake, fake + 2, fake, fake, fake, fake, fake, fake, None) == -1
+    # the integer sums over the groups come from the generic and the tiled kernel only: refused, nothing launched
+    assert L.mixllm_debug_channel_sums(C.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, fake, 2, None) == -2
+    # the 128 x 128 block shape is not built for activation scales per (token, group)
+    dg = binding._desc(300, 256, 64, 8, act_group=128)
+    assert L.mixllm_mixed_linear_path(C.byref(dg), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, 0, 10, None) == -2
     assert L.mixllm_quantize_activations(C.byref(d), fake + 2, fake, fake, None) == -1
     # bad path value
-    assert L.mixllm_mixed_linear_path(C.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, 0, 9, None) == -1
+    assert L.mixllm_mixed_linear_path(C.byref(d), fake, fake, fake, fake, fake, fake, fake, fake, fake, None, 0, 11, None) == -1
     # the decode path refuses M > 16; M = 0 is a no-op that succeeds without a device
     d0 = binding._desc(0, 256, 64, 8)
     assert L.mixllm_mixed_linear(C.byref(d0), None, None, None, None, None, None, None, None, None, None, 0, None) == 0
