@@ -15,7 +15,8 @@
  *     return means nothing ran.  No function throws.
  *   - Unless a parameter says "host", every data pointer is DEVICE memory, owned by
  *     the caller, 16-byte aligned, of the size mixllm_query_sizes() reports.  The
- *     library allocates no memory and keeps no state between calls.
+ *     library allocates no memory and keeps no state between calls (one entry point,
+ *     mixllm_mixed_linear_fp16_static, keeps its scratch in a device array of its own).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued on it and the call returns without synchronizing and without blocking
  *     copies: no entry point waits for the device.
@@ -43,6 +44,8 @@ extern "C" {
 /* Largest K: an 8-bit channel with one scale keeps a single int32 sum over all of K, and
  * K * 127 * 127 must stay below 2^31. */
 #define MIXLLM_MAX_K 131072
+/* Bytes of the device array behind mixllm_mixed_linear_fp16_static. */
+#define MIXLLM_STATIC_SCRATCH_BYTES (8u * 1024u * 1024u + 256u * 1024u)
 
 enum {
     MIXLLM_OK = 0,
@@ -204,6 +207,25 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
                              const void *packed_w8, const void *scales4, const void *scales8,
                              const void *zeros4, const int32_t *feature_perm, void *y, void *workspace,
                              size_t workspace_bytes, void *stream);
+
+/*
+ * mixllm_mixed_linear_fp16 for callers that can neither allocate device memory nor hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments without the workspace, same kernels, same results; the scratch area (xq, xscale)
+ * is a device array inside the library, MIXLLM_STATIC_SCRATCH_BYTES long, that every GPU the
+ * library runs on holds until the process ends.  The call allocates nothing.
+ *   - A shape whose scratch (mixllm_query_sizes().workspace_bytes) exceeds the array is refused
+ *     with MIXLLM_EWORKSPACE before anything is enqueued.  8 MiB + 256 KiB covers M K up to
+ *     8 Mi activation values, e.g. 2048 tokens of K = 4096 with either scale granularity.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different
+ *     streams, or different threads) race on it.  Calls on one stream are ordered and safe.
+ *     Nothing in the array has to start at zero: the quantizer writes every byte the linear
+ *     reads, whatever an earlier call left there.
+ * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP.  M = 0 is a no-op.
+ */
+int mixllm_mixed_linear_fp16_static(const mixllm_desc *d, const void *x, const void *packed_w4,
+                                    const void *packed_w8, const void *scales4, const void *scales8,
+                                    const void *zeros4, const int32_t *feature_perm, void *y, void *stream);
 
 /* Same as mixllm_mixed_linear, with the kernel chosen by the caller (MIXLLM_PATH_*); for tests and benchmarks. */
 int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void *xscale,

@@ -64,6 +64,7 @@ def lib():
         L.mixllm_debug_group_partials.argtypes = [C.POINTER(_Desc)] + [_VP] * 6 + [C.c_int, _VP]
         L.mixllm_debug_channel_sums.argtypes = [C.POINTER(_Desc)] + [_VP] * 9 + [C.c_int, _VP]
         L.mixllm_mixed_linear_fp16.argtypes = [C.POINTER(_Desc)] + [_VP] * 9 + [C.c_size_t, _VP]
+        L.mixllm_mixed_linear_fp16_static.argtypes = [C.POINTER(_Desc)] + [_VP] * 9
         L.mixllm_channel_salience.argtypes = [C.POINTER(_Desc), _VP, _VP, C.c_float, C.c_int, _VP, _VP]
         L.mixllm_select_salient_workspace.argtypes = [C.c_int32]
         L.mixllm_select_salient_workspace.restype = C.c_size_t
@@ -77,7 +78,7 @@ def lib():
         for name in ("mixllm_query_sizes", "mixllm_build_feature_perm", "mixllm_quantize_weights",
                      "mixllm_pack_weights", "mixllm_unpack_weights", "mixllm_quantize_activations",
                      "mixllm_mixed_linear", "mixllm_mixed_linear_path", "mixllm_debug_group_partials",
-                     "mixllm_mixed_linear_fp16", "mixllm_debug_channel_sums"):
+                     "mixllm_mixed_linear_fp16", "mixllm_mixed_linear_fp16_static", "mixllm_debug_channel_sums"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -285,6 +286,17 @@ def linear_fp16(x: torch.Tensor, L: PackedLayer, act_group=None, out=None, works
                                           _ptr(L.z4), _ptr(L.perm), _ptr(y), _ptr(workspace), wb, _stream()),
            "mixllm_mixed_linear_fp16")
     return y
+
+
+def linear_fp16_static(x: torch.Tensor, L: PackedLayer, out: torch.Tensor, act_group=None) -> torch.Tensor:
+    """mixllm_mixed_linear_fp16_static: the same as linear_fp16 with the scratch inside the library; the
+    caller brings the output tensor, and nothing is allocated on the way."""
+    assert x.dtype == torch.float16 and x.dim() == 2 and out.dtype == torch.float16 and out.shape == (x.shape[0], L.N)
+    d = L.desc(x.shape[0], act_group)
+    _check(lib().mixllm_mixed_linear_fp16_static(C.byref(d), _ptr(x), _ptr(L.w4), _ptr(L.w8), _ptr(L.s4), _ptr(L.s8),
+                                                 _ptr(L.z4), _ptr(L.perm), _ptr(out), _stream()),
+           "mixllm_mixed_linear_fp16_static")
+    return out
 
 
 def channel_salience(W: torch.Tensor, G: torch.Tensor, out=None, weight: float = 1.0, accumulate: bool = False) -> torch.Tensor:

@@ -8,6 +8,11 @@
 
 using namespace mixllm;
 
+// Scratch of mixllm_mixed_linear_fp16_static (xq, then xscale): one array per GPU, held by the
+// loaded code object until the process ends.  In host code the name is only a handle: the device
+// address comes from hipGetSymbolAddress, per device (static_scratch_ptr below).
+static __device__ __align__(256) uint8_t scratch[MIXLLM_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 inline size_t round_up_sz(size_t a, size_t b) { return (a + b - 1) / b * b; }
@@ -379,6 +384,51 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
 {
     return linear_from_fp16(d, x, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, y, workspace,
                             workspace_bytes, (hipStream_t)stream);
+}
+
+// Device address of `scratch` on the current device; looked up once per device, with that device
+// current, and kept.  Returns nullptr (and the HIP error in *err) when the lookup fails.
+static void *static_scratch_ptr(hipError_t *err)
+{
+    static void *ptr[64] = {nullptr};
+    static std::mutex mu;
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= 64) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *q = nullptr;
+        *err = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !q) {
+            if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        ptr[dev] = q;
+    }
+    return ptr[dev];
+}
+
+int mixllm_mixed_linear_fp16_static(const mixllm_desc *d, const void *x, const void *packed_w4, const void *packed_w8,
+                                    const void *scales4, const void *scales8, const void *zeros4,
+                                    const int32_t *feature_perm, void *y, void *stream)
+{
+    if (int rc = check_desc(d)) return rc;
+    if (d->M == 0) return MIXLLM_OK;
+    mixllm_sizes s;
+    sizes_of(*d, s);
+    // refused before anything is looked up or enqueued; a shape that runs as one kernel does not
+    // touch the array, but the limit is the same for every call so that it does not depend on
+    // which kernel the library happens to choose
+    if (s.workspace_bytes > (size_t)MIXLLM_STATIC_SCRATCH_BYTES) return MIXLLM_EWORKSPACE;
+    hipError_t e = hipSuccess;
+    void *area = static_scratch_ptr(&e);
+    if (!area) return MIXLLM_EHIP;
+    return linear_from_fp16(d, x, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, y, area,
+                            (size_t)MIXLLM_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
 }
 
 int mixllm_channel_salience(const mixllm_desc *d, const void *W, const void *G, float weight, int accumulate,
