@@ -9,8 +9,13 @@ rotated over several copies so that no step finds its weights in the 256 MB memo
 Default run:  decode leg (M = 1; the `value` of the JSON line, in GB/s of algorithmic bytes)
 followed by short extra legs (other decode M, prefill M = 2048 in TOPS) that are reported in
 the same JSON line under "sweep" / "prefill".  `--workload prefill` makes the prefill leg the
-primary one.  One JSON line is printed on stdout; progress goes to stderr.
+primary one; `--workload 70b` runs the Llama-3.1-70B-shaped block over M in {1, 16, 64, 256, 2048};
+`--workload stack` runs 32 blocks back to back with an uneven 8-bit share per layer at M in {1, 256}.
+Every leg carries mean, median and minimum time per step, the time of its dominant kernel, and both
+as fractions of the roofline min(HBM, int8 MFMA) for its algorithmic bytes and operations.
+One JSON line is printed on stdout; progress goes to stderr.
 """
+import hashlib
 import argparse
 import json
 import os
@@ -39,6 +44,32 @@ def layer_alg_bytes(K, N, n8, M):
 
 def quant_alg_bytes(K, M):
     return 2 * M * K + M * K + 2 * M
+
+
+def roofline_seconds(nbytes, ops):
+    """Time the roofline allows: whichever of the HBM stream and the int8 MFMA work takes longer."""
+    return max(nbytes / (HBM_PEAK_GBS * 1e9), ops / (INT8_PEAK_TOPS * 1e12))
+
+
+def roofline_entry(nbytes, ops, seconds):
+    """A `roofline` object for work of `nbytes` algorithmic bytes and `ops` operations done in `seconds`."""
+    t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), ops / (INT8_PEAK_TOPS * 1e12)
+    if t_hbm >= t_mfma:
+        ach, peak, unit, bound = nbytes / seconds / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
+    else:
+        ach, peak, unit, bound = ops / seconds / 1e12, INT8_PEAK_TOPS, "TOP/s", "mfma"
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+            "frac_of_min_hbm_mfma": max(t_hbm, t_mfma) / seconds}
+
+
+def source_sha(*names):
+    """sha256 (16 hex digits) over the kernel sources a stored counter figure belongs to."""
+    h = hashlib.sha256()
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2412_14590_amd", "csrc")
+    for n in names:
+        with open(os.path.join(root, n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def salience_bench(args, torch, mx, synth, dev):
@@ -99,8 +130,8 @@ def salience_bench(args, torch, mx, synth, dev):
 def share_sweep(args, torch, mx, synth, dev):
     """The grid of the paper's single-linear study (Sec. 5.2: K = 4096, N in {4096, 14336},
     8-bit shares 0 / 10 / 20 / 50 / 100 %, token counts 1..1024), on seeded synthetic weights:
-    time of the whole path from fp16 activations (quantizer + mixed linear), of the linear alone,
-    and of torch's fp16 matmul on the same GPU as the float16 reference of that study.  Every
+    time of the whole path from fp16 activations (quantizer + mixed linear) and of the linear alone,
+    each against the roofline min(HBM, int8 MFMA) of its algorithmic bytes and operations.  Every
     figure is the mean over `reps` launches replayed from a HIP graph, weights rotating over
     enough copies to stay out of the memory-side cache."""
     K, rows = 4096, []
@@ -131,17 +162,10 @@ def share_sweep(args, torch, mx, synth, dev):
 
     for N in (4096, 14336):
         W = torch.from_numpy(synth.make_w(N, K, seed=0, tag=f"w/sweep{N}")).to(dev)
-        n_f16 = max(2, -(-2 * MALL_BYTES // (2 * N * K)))
-        W16 = [W] + [W.clone() for _ in range(n_f16 - 1)]
-        f16_us = {}
-        for M in Ms:
-            x = torch.from_numpy(synth.make_x(M, K, seed=7, tag="x/sweep")).to(dev)
-            y16 = torch.empty((M, N), dtype=torch.float16, device=dev)
-            f16_us[M] = graph_time(lambda i: torch.matmul(x, W16[i % n_f16].t(), out=y16), 40) * 1e6
+        order = synth.salience_order(W.cpu().numpy(), seed=0)
         for f in shares:
             n8 = synth.n8_for(N, f)
-            sal = synth.select_salient(W.cpu().numpy(), n8, seed=0) if 0 < n8 < N else np.arange(n8, dtype=np.int32)
-            L0 = mx.quantize_weights(W, sal)
+            L0 = mx.quantize_weights(W, np.sort(order[:n8]).astype(np.int32))
             n_c = max(2, -(-2 * MALL_BYTES // L0.weight_bytes()))
             Ls = [L0] + [L0.clone() for _ in range(n_c - 1)]
             for M in Ms:
@@ -151,15 +175,15 @@ def share_sweep(args, torch, mx, synth, dev):
                 ws = torch.empty(mx.query_sizes(M, K, N, n8)["workspace_bytes"], dtype=torch.uint8, device=dev)
                 reps = 60 if M <= 64 else 30
                 t_path = graph_time(lambda i: mx.linear_fp16(x, Ls[i % n_c], out=y, workspace=ws), reps)
-                t_lin = graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], out=y), reps)
+                t_lin = graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], out=y, workspace=ws), reps)
+                nb, ops = layer_alg_bytes(K, N, n8, M), 2.0 * M * N * K
                 row = {"N": N, "share8": f, "n8": n8, "M": M, "path_us": t_path * 1e6, "linear_us": t_lin * 1e6,
-                       "torch_fp16_us": f16_us[M], "speedup_vs_fp16": f16_us[M] / (t_path * 1e6),
-                       "linear_GBps": layer_alg_bytes(K, N, n8, M) / t_lin / 1e9,
-                       "linear_TOPS": 2.0 * M * N * K / t_lin / 1e12}
+                       "linear_GBps": nb / t_lin / 1e9, "linear_TOPS": ops / t_lin / 1e12,
+                       "roofline": roofline_entry(nb, ops, t_lin)}
                 rows.append(row)
                 log(f"[sweep] N={N} share={f:.2f} M={M}: path {row['path_us']:.1f} us, linear {row['linear_us']:.1f} us, "
-                    f"fp16 {row['torch_fp16_us']:.1f} us, x{row['speedup_vs_fp16']:.2f}, "
-                    f"{row['linear_GBps']:.0f} GB/s, {row['linear_TOPS']:.0f} TOPS")
+                    f"{row['linear_GBps']:.0f} GB/s, {row['linear_TOPS']:.0f} TOPS, "
+                    f"{row['roofline']['frac_of_min_hbm_mfma']:.2f} of min(HBM, MFMA)")
             del Ls
             torch.cuda.empty_cache()
     ref_row = next(r for r in rows if r["N"] == 14336 and r["share8"] == 0.10 and r["M"] == 1)
@@ -168,7 +192,7 @@ def share_sweep(args, torch, mx, synth, dev):
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
             "config": {"workload": "single linear K=4096, N in {4096, 14336}, 8-bit share 0..100 %, M in {1, 16, 64, 256, 1024}; "
                                    "value = the linear at N=14336, 10 % 8-bit, M=1"},
-            "rows": rows}
+            "roofline": ref_row["roofline"], "rows": rows}
 
 
 def main():
@@ -176,11 +200,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["decode", "prefill", "share-sweep", "salience"], default="decode",
-                    help="share-sweep: single linears K=4096, N in {4096, 14336}, 8-bit shares 0..100 %%, M = 1..1024 "
-                         "(the grid of the paper's single-linear study, Sec. 5.2); salience: the global precision "
-                         "search of Sec. 3.2 (channel salience of the gate+up layer, selection over a 32-block stack)")
-    ap.add_argument("--m", type=int, default=None, help="tokens (default 1 for decode, 2048 for prefill)")
+    ap.add_argument("--workload", choices=["decode", "prefill", "70b", "stack", "share-sweep", "salience"], default="decode",
+                    help="decode / prefill: one Llama-3-8B-shaped block at M = 1 / 2048 (plus the other token counts as extra "
+                         "legs); 70b: one Llama-3.1-70B-shaped block, M in {1, 16, 64, 256, 2048}; stack: 32 8B-shaped blocks "
+                         "back to back with an uneven 8-bit share per layer, M in {1, 256}; share-sweep: single linears "
+                         "K=4096, N in {4096, 14336}, 8-bit shares 0..100 %%, M = 1..1024 (the grid of the paper's "
+                         "single-linear study, Sec. 5.2); salience: the global precision search of Sec. 3.2")
+    ap.add_argument("--m", type=int, default=None, help="tokens of the primary leg (default 1; 2048 for --workload prefill)")
     ap.add_argument("--no-extras", action="store_true", help="primary leg only (for profiling)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     ap.add_argument("--copy-probe", action="store_true",
@@ -205,34 +231,54 @@ def main():
     if args.workload == "share-sweep":
         print(json.dumps(share_sweep(args, torch, mx, synth, dev)), flush=True)
         return
-    M0 = args.m if args.m is not None else (1 if args.workload == "decode" else 2048)
+    M0 = args.m if args.m is not None else (2048 if args.workload == "prefill" else 1)
 
-    # ---- inputs (seeded, synthetic, Llama-3-8B shaped) -----------------------------------
+    # ---- inputs (seeded, synthetic) --------------------------------------------------------
+    # `layers`: the linears of one step, in launch order.  decode / prefill / 70b: the four linears
+    # of one decoder block, 10 % of the channels at 8 bits; stack: 32 blocks of the 8B shapes with
+    # the per-layer 8-bit share of synth.uneven_fractions (0..40 %, mean 10 %) - the fp16 weights
+    # of a layer kind are drawn once and shared by the 32 blocks, each block quantizes them with
+    # its own share (what is measured is the kernels' balance across shares, not the values).
     t0 = time.time()
-    layers = []
-    for name, K, N, sigma, n_out in synth.model_layers("8b"):
-        lay = synth.make_layer(name, K, N, sigma=sigma, n_outlier_rows=n_out, seed=0)
+    model = "70b" if args.workload == "70b" else "8b"
+    kinds = {}
+    for name, K, N, sigma, n_out in synth.model_layers(model):
+        W = synth.make_w(N, K, sigma, n_out, seed=0, tag="w/" + name)
+        kinds[name] = (K, N, W, synth.salience_order(W, seed=0))
+        log(f"[bench] weights {name}: K={K} N={N}  ({time.time() - t0:.1f}s)")
+    if args.workload == "stack":
+        shares = synth.uneven_fractions(32, seed=0)
+        specs = [(f"{name}.{blk}", name, shares[(blk, name)]) for blk in range(32) for name in kinds]
+    else:
+        specs = [(name, name, 0.10) for name in kinds]
+    layers, packed0 = [], []
+    for lname, kind, f in specs:
+        K, N, W, order = kinds[kind]
+        n8 = synth.n8_for(N, f)
+        lay = synth.LayerInputs(lname, K, N, n8, W, np.sort(order[:n8]).astype(np.int32))
         layers.append(lay)
-        log(f"[bench] layer {name}: K={K} N={N} n8={lay.n8}  ({time.time() - t0:.1f}s)")
-    packed0 = [mx.quantize_weights(torch.from_numpy(l.W).to(dev), l.salient_idx) for l in layers]
+    Wd = {k: torch.from_numpy(v[2]).to(dev) for k, v in kinds.items()}
+    packed0 = [mx.quantize_weights(Wd[kind], lay.salient_idx) for lay, (_, kind, _) in zip(layers, specs)]
     torch.cuda.synchronize()
+    del Wd
     set_bytes = sum(p.weight_bytes() for p in packed0)
-    n_copies = max(2, -(-2 * MALL_BYTES // set_bytes))      # rotate over >= 512 MB of weights
+    n_copies = max(1 if set_bytes >= 2 * MALL_BYTES else 2, -(-2 * MALL_BYTES // set_bytes))   # >= 512 MB between reuses
     copies = [packed0] + [[p.clone() for p in packed0] for _ in range(n_copies - 1)]
-    log(f"[bench] packed weights {set_bytes / 1e6:.1f} MB per block, {n_copies} rotating copies")
+    log(f"[bench] {len(layers)} linears per step, packed weights {set_bytes / 1e6:.1f} MB, {n_copies} rotating copies")
 
     # granularity of the scales: the measured default (one activation scale per token, one scale per
     # 8-bit channel) or the paper's (both per group of 128, Sec. 4.1); the paper's gets a leg of its own
     mode = {"copies": copies, "act_group": None, "w8_group": None}
 
     def make_acts(M):
-        xs_ = [torch.from_numpy(synth.make_x(M, l.K, seed=7, tag="x/" + l.name)).to(dev) for l in layers]
-        bufs = [(torch.empty((M, l.K), dtype=torch.int8, device=dev),
-                 torch.empty((M, 1), dtype=torch.float16, device=dev),
-                 torch.empty((M, l.N), dtype=torch.float16, device=dev),
-                 torch.empty(mx.query_sizes(M, l.K, l.N, l.n8, mode["act_group"], mode["w8_group"])["workspace_bytes"],
-                             dtype=torch.uint8, device=dev))
-                for l in layers]
+        xk = {k: torch.from_numpy(synth.make_x(M, v[0], seed=7, tag="x/" + k)).to(dev) for k, v in kinds.items()}
+        xs_ = [xk[kind] for _, kind, _ in specs]
+        ws_bytes = max(mx.query_sizes(M, l.K, l.N, l.n8, mode["act_group"], mode["w8_group"])["workspace_bytes"] for l in layers)
+        yk = {k: torch.empty((M, v[1]), dtype=torch.float16, device=dev) for k, v in kinds.items()}
+        wsp = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # (None, None, y, workspace) per linear: the linears of a step run one after the other on one
+        # stream, so layers of one kind share an output tensor and all share the workspace
+        bufs = [(None, None, yk[specs[li][1]], wsp) for li in range(len(layers))]
         return xs_, bufs
 
     # Order of the linear launches as the GPU executes them (layer indices; a captured graph adds
@@ -252,16 +298,20 @@ def main():
             note(li)
 
     def time_steps(M, steps, warmup):
-        """Seconds per step.  Decode steps are launch bound when driven from Python (8 ctypes
-        calls of ~5 us each), so n_copies consecutive steps (one per weight copy) are captured
-        into one HIP graph and replayed; the graph's output is checked against eager once."""
+        """Seconds per step: {"mean", "median", "min"}.  Decode steps are launch bound when driven from
+        Python (8 ctypes calls of ~5 us each), so n_copies consecutive steps (one per weight copy) are
+        captured into one HIP graph and replayed; the graph's output is checked against eager launches.
+        The mean is wall time over all timed steps between two synchronizations; median and minimum are
+        over the timed units (one graph replay = n_copies steps, or one eager step), each between two
+        events on the launch stream."""
         xs_, bufs = make_acts(M)
         use_graph = not args.no_graph and M <= 256      # launch bound when driven from Python up to a few hundred tokens
         for i in range(max(warmup, n_copies) if not use_graph else n_copies):
             step(i, xs_, bufs)
         torch.cuda.synchronize()
         if use_graph:
-            eager = [b[2].clone() for b in bufs]          # y of the last eager step (copy n_copies - 1)
+            last = {id(b[2]): b[2] for b in bufs}
+            eager = {k: v.clone() for k, v in last.items()}          # y of the last eager step (copy n_copies - 1)
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             graph = torch.cuda.CUDAGraph()
@@ -273,34 +323,39 @@ def main():
             captured, recording[0] = recording[0], None
             torch.cuda.current_stream().wait_stream(side)
 
-            def replay_steps():
+            def unit():
                 graph.replay()
                 executed.extend(captured)
 
             for rep in range(3):                          # replay check, with eager work in between
-                for b in bufs:
-                    b[2].zero_()
-                replay_steps()
+                for v in last.values():
+                    v.zero_()
+                unit()
                 torch.cuda.synchronize()
-                for e, b in zip(eager, bufs):
-                    assert torch.equal(e, b[2]), "HIP graph replay differs from eager launch"
-            nrep_w, nrep = max(1, warmup // n_copies), max(1, -(-steps // n_copies))
-            for _ in range(nrep_w):
-                replay_steps()
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            for _ in range(nrep):
-                replay_steps()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t) / (nrep * n_copies)
-        for i in range(warmup):
-            step(i, xs_, bufs)
+                for k, v in last.items():
+                    assert torch.equal(eager[k], v), "HIP graph replay differs from eager launch"
+            per_unit, n_warm, n_units = n_copies, max(1, warmup // n_copies), max(1, -(-steps // n_copies))
+        else:
+            count = [0]
+
+            def unit():
+                step(count[0], xs_, bufs)
+                count[0] += 1
+
+            per_unit, n_warm, n_units = 1, warmup, steps
+        for _ in range(n_warm):
+            unit()
         torch.cuda.synchronize()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_units + 1)]
         t = time.perf_counter()
-        for i in range(steps):
-            step(i, xs_, bufs)
+        evs[0].record()
+        for k in range(n_units):
+            unit()
+            evs[k + 1].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) / steps
+        mean = (time.perf_counter() - t) / (n_units * per_unit)
+        per = np.array([evs[k].elapsed_time(evs[k + 1]) for k in range(n_units)]) * 1e-3 / per_unit
+        return {"mean": mean, "median": float(np.median(per)), "min": float(per.min())}
 
     def time_dominant(M, reps, li):
         """Average duration of one launch of the linear kernel of layer `li`: `reps` launches
@@ -310,16 +365,20 @@ def main():
         has to agree with.  Also returned: the mean over launches that each have their own event
         pair (includes ~2 us of event and launch handling per launch)."""
         xs_, bufs = make_acts(M)
-        xq, xsc, y, ws = bufs[li]
-        mx.quantize_activations(xs_[li], out=(xq, xsc))
+        _, _, y, ws = bufs[li]
+        xq, xsc = mx.quantize_activations(xs_[li])
+        # copies of this layer's weights to rotate over: at least 512 MB between two uses of one
+        own = [c[li] for c in copies]
+        while sum(p.weight_bytes() for p in own) < 2 * MALL_BYTES:
+            own.append(own[0].clone())
 
         def one(i):
             # the launch the step makes for this layer: for a single token the decode kernel
             # that quantizes its own activations, otherwise the linear after the quantizer
             if M == 1:
-                mx.linear_fp16(xs_[li], copies[i % n_copies][li], out=y, workspace=ws)
+                mx.linear_fp16(xs_[li], own[i % len(own)], out=y, workspace=ws)
             else:
-                mx.mixed_linear(xq, xsc, copies[i % n_copies][li], out=y)
+                mx.mixed_linear(xq, xsc, own[i % len(own)], out=y, workspace=ws)
             note(li)
 
         for i in range(max(10, reps)):      # warm: clocks settle over tens of milliseconds at large M
@@ -370,55 +429,69 @@ def main():
     def step_ops(M):
         return sum(2.0 * M * l.K * l.N for l in layers)
 
-    dom = max(range(len(layers)), key=lambda i: layers[i].K * layers[i].N)   # gate_up
+    dom = max(range(len(layers)), key=lambda i: (layers[i].K * layers[i].N, layers[i].n8))   # gate_up (stack: its largest 8-bit share)
 
     def leg(M, steps, warmup, reps):
         first = len(executed)
-        sec = time_steps(M, steps, warmup)
+        t = time_steps(M, steps, warmup)
+        sec = t["mean"]
         k_graph, k_pair = time_dominant(M, reps, dom)
         launches = executed[first:]
         l = layers[dom]
-        out = {"M": M, "launches": launches, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9,
-               "TOPS": step_ops(M) / sec / 1e12,
+        kb, ko = layer_alg_bytes(l.K, l.N, l.n8, M), 2.0 * M * l.K * l.N
+        out = {"M": M, "launches": launches, "ms_per_step": sec * 1e3, "ms_per_step_median": t["median"] * 1e3,
+               "ms_per_step_min": t["min"] * 1e3, "GBps": step_bytes(M) / sec / 1e9, "TOPS": step_ops(M) / sec / 1e12,
+               # the step (quantizers + linears of all layers) and its dominant kernel against min(HBM, int8 MFMA)
+               "step_roofline": roofline_entry(step_bytes(M), step_ops(M), sec),
                "dominant_kernel": {"layer": l.name, "us_per_launch": k_graph * 1e6,
                                    "us_with_own_event_pair": k_pair * 1e6,
-                                   "GBps": layer_alg_bytes(l.K, l.N, l.n8, M) / k_graph / 1e9,
-                                   "TOPS": 2.0 * M * l.K * l.N / k_graph / 1e12}}
-        log(f"[bench] M={M}: {out['ms_per_step']:.4f} ms/step, {out['GBps']:.0f} GB/s, {out['TOPS']:.1f} TOPS; "
-            f"{l.name} kernel {k_graph * 1e6:.1f} us per launch ({k_pair * 1e6:.1f} with its own event pair)")
+                                   "GBps": kb / k_graph / 1e9, "TOPS": ko / k_graph / 1e12,
+                                   "roofline": roofline_entry(kb, ko, k_graph)}}
+        log(f"[bench] M={M}: {out['ms_per_step']:.4f} ms/step (median {out['ms_per_step_median']:.4f}, min "
+            f"{out['ms_per_step_min']:.4f}), {out['GBps']:.0f} GB/s, {out['TOPS']:.1f} TOPS, "
+            f"{out['step_roofline']['frac_of_min_hbm_mfma']:.2f} of min(HBM, MFMA); {l.name} kernel {k_graph * 1e6:.1f} us "
+            f"per launch ({k_pair * 1e6:.1f} with its own event pair), {out['dominant_kernel']['roofline']['frac_of_min_hbm_mfma']:.2f}")
         return out
 
     decode_like = M0 <= 16
     primary = leg(M0, args.steps, args.warmup if decode_like else max(args.warmup, 40), min(args.steps, 200) if decode_like else 30)
     l = layers[dom]
-    if decode_like:
-        roof = {"bound": "hbm", "achieved": primary["dominant_kernel"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": primary["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof = dict(primary["dominant_kernel"]["roofline"])
     # HBM bytes per launch of that kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-    # same command (scaled by a plain copy of known size); measured offline, kept under profiles/
+    # same command (scaled by a plain copy of known size); measured offline and kept under profiles/
+    # together with a hash of the kernel's sources: a figure measured on other sources is not reported
     roof["traffic"] = None
     tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        key = ("decode" if decode_like else "prefill") + f"_m{M0}_{l.name}"
-        roof["traffic"] = json.load(open(tpath)).get(key)
-    roof["algorithmic"] = layer_alg_bytes(l.K, l.N, l.n8, M0) if decode_like else 2.0 * M0 * l.K * l.N
+    if os.path.exists(tpath) and args.workload in ("decode", "prefill"):
+        rec = json.load(open(tpath)).get(("decode" if decode_like else "prefill") + f"_m{M0}_{l.name}")
+        if isinstance(rec, dict):
+            srcs = rec.get("sources", [])
+            if rec.get("sources_sha16") == source_sha(*srcs):
+                roof["traffic"] = rec.get("bytes")
+            else:
+                roof["traffic_note"] = "stored counter figure belongs to other kernel sources: not reported"
+    roof["algorithmic"] = layer_alg_bytes(l.K, l.N, l.n8, M0) if roof["bound"] == "hbm" else 2.0 * M0 * l.K * l.N
     roof["kernel"] = f"mixed_linear {'decode' if decode_like else 'prefill'} path, layer {l.name} K={l.K} N={l.N} M={M0}"
     roof["us_per_launch"] = primary["dominant_kernel"]["us_per_launch"]
 
+    what = {"decode": "Llama-3-8B-shaped decoder-block linears (QKV, O, gate+up, down)",
+            "prefill": "Llama-3-8B-shaped decoder-block linears (QKV, O, gate+up, down)",
+            "70b": "Llama-3.1-70B-shaped decoder-block linears (QKV, O, gate+up, down)",
+            "stack": "32 Llama-3-8B-shaped decoder blocks back to back (128 linears), 8-bit share per layer 0..40 % (mean 10 %)"}
     result = {
         "metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)",
         "value": primary["GBps"] if decode_like else primary["TOPS"],
         "unit": "GB/s" if decode_like else "TOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": primary["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": primary["ms_per_step"], "ms_per_step_median": primary["ms_per_step_median"],
+        "ms_per_step_min": primary["ms_per_step_min"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"Llama-3-8B-shaped decoder-block linears (QKV, O, gate+up, down), "
-                               f"{'decode' if decode_like else 'prefill'} M={M0}, 10% int8 channels, int4 g128, "
+        "config": {"workload": f"{what[args.workload]}, {'decode' if decode_like else 'prefill'} M={M0}, "
+                               f"{'10% int8 channels' if args.workload != 'stack' else 'uneven int8 share'}, int4 g128, "
                                f"per-token int8 activations, fp16 out",
                    "M": M0, "weight_copies_rotated": n_copies},
         "step_GBps": primary["GBps"], "step_TOPS": primary["TOPS"],
+        "step_roofline": primary["step_roofline"],
         "roofline": roof,
     }
     # order of the primary leg's linear launches, run-length encoded: [[layer names of one period], repeats]
@@ -432,7 +505,7 @@ def main():
         n = 0
         while seq[i:i + len(pat)] == pat:
             n, i = n + 1, i + len(pat)
-        runs.append([[layers[j].name for j in pat], n])
+        runs.append([[layers[j].name for j in pat] if len(pat) <= 8 else f"all {len(pat)} linears in order", n])
     result["linear_launch_order"] = runs
 
     # ---- measured ceilings of this GPU (context for the published peaks) ----------------------
@@ -453,32 +526,42 @@ def main():
 
     # ---- extra legs ------------------------------------------------------------------------
     if not args.no_extras:
+        if args.workload == "70b":
+            extra_ms = [m for m in (1, 16, 64, 256, 2048) if m != M0]
+        elif args.workload == "stack":
+            extra_ms = [m for m in (1, 256) if m != M0]
+        else:
+            extra_ms = [2, 4, 8, 16, 64, 256] if decode_like else [512, 8192]
         sweep = []
-        for M in ([2, 4, 8, 16, 64, 256] if decode_like else [512, 8192]):
+        for M in extra_ms:
             small = M <= 16
             sweep.append(leg(M, max(20, args.steps // 4) if small else 40, 5 if small else 40, 50 if small else 30))
-        other = leg(2048 if decode_like else 1, 40 if decode_like else 100, 40 if decode_like else 3, 30)
-        for extra in sweep + [other]:
+        if args.workload in ("decode", "prefill"):
+            other = leg(2048 if decode_like else 1, 40 if decode_like else 100, 40 if decode_like else 3, 30)
+            other["roofline"] = other["dominant_kernel"]["roofline"]
+            result["prefill" if decode_like else "decode"] = other
+            sweep_all = sweep + [other]
+        else:
+            sweep_all = sweep
+        for extra in sweep_all:
             del extra["launches"]
         result["sweep"] = sweep
-        key = "prefill" if decode_like else "decode"
-        if decode_like:
-            other["roofline"] = {"bound": "mfma", "achieved": other["dominant_kernel"]["TOPS"], "peak": INT8_PEAK_TOPS,
-                                 "unit": "TOP/s", "frac": other["dominant_kernel"]["TOPS"] / INT8_PEAK_TOPS}
-        else:
-            other["roofline"] = {"bound": "hbm", "achieved": other["dominant_kernel"]["GBps"], "peak": HBM_PEAK_GBS,
-                                 "unit": "GB/s", "frac": other["dominant_kernel"]["GBps"] / HBM_PEAK_GBS}
-        result[key] = other
+    if not args.no_extras and args.workload in ("decode", "prefill"):
         # the paper's granularity (activation scales per token and group, 8-bit weight scales per
         # group): the whole step, same shapes, same launch method
-        packed_p = [mx.quantize_weights(torch.from_numpy(l.W).to(dev), l.salient_idx, w8_group=128) for l in layers]
+        Wd = {k: torch.from_numpy(v[2]).to(dev) for k, v in kinds.items()}
+        packed_p = [mx.quantize_weights(Wd[kind], lay.salient_idx, w8_group=128) for lay, (_, kind, _) in zip(layers, specs)]
+        del Wd
         mode.update(copies=[packed_p] + [[p.clone() for p in packed_p] for _ in range(n_copies - 1)],
                     act_group=128, w8_group=128)
         gran = []
         for M in (1, 16, 2048):
             small = M <= 16
-            sec = time_steps(M, 50 if small else 40, 5 if small else 40)
-            gran.append({"M": M, "ms_per_step": sec * 1e3, "GBps": step_bytes(M) / sec / 1e9, "TOPS": step_ops(M) / sec / 1e12})
+            t = time_steps(M, 50 if small else 40, 5 if small else 40)
+            sec = t["mean"]
+            gran.append({"M": M, "ms_per_step": sec * 1e3, "ms_per_step_median": t["median"] * 1e3, "ms_per_step_min": t["min"] * 1e3,
+                         "GBps": step_bytes(M) / sec / 1e9, "TOPS": step_ops(M) / sec / 1e12,
+                         "step_roofline": roofline_entry(step_bytes(M), step_ops(M), sec)})
             log(f"[bench] scales per group of 128 (activations and 8-bit weights), M={M}: {sec * 1e3:.4f} ms/step")
         result["paper_granularity"] = {"act_group": 128, "w8_group": 128, "legs": gran,
                                        "note": "GBps / TOPS use the algorithmic bytes / operations of the default granularity"}
@@ -489,9 +572,10 @@ def main():
         from oracle import ref
         t1 = time.time()
         Ms = M0 if decode_like else 8       # prefill: a sample of 8 token rows of the same layers
-        Ls = [ref.quantize_weights(l.W, l.salient_idx) for l in layers]
+        sample = list(range(min(4, len(layers))))     # stack: the four linears of the first block
+        Ls = [ref.quantize_weights(layers[i].W, layers[i].salient_idx) for i in sample]
         log(f"[bench] oracle weight quantization {time.time() - t1:.1f}s (not timed)")
-        xs_h = [synth.make_x(Ms, l.K, seed=7, tag="x/" + l.name) for l in layers]
+        xs_h = [synth.make_x(Ms, layers[i].K, seed=7, tag="x/" + specs[i][1]) for i in sample]
         reps, t_cpu = 0, 0.0
         while t_cpu < 10.0 and reps < 5000:
             t = time.perf_counter()
@@ -501,10 +585,12 @@ def main():
             t_cpu += time.perf_counter() - t
             reps += 1
         sec = t_cpu / reps
-        val = (step_bytes(Ms) / sec / 1e9) if decode_like else (step_ops(Ms) / sec / 1e12)
+        sb = sum(layer_alg_bytes(layers[i].K, layers[i].N, layers[i].n8, Ms) + quant_alg_bytes(layers[i].K, Ms) for i in sample)
+        so = sum(2.0 * Ms * layers[i].K * layers[i].N for i in sample)
+        val = (sb / sec / 1e9) if decode_like else (so / sec / 1e12)
         result["cpu_baseline"] = {"value": val, "unit": result["unit"], "cores": ref.num_threads(), "kind": "oracle",
-                                  "sample": f"{reps} passes of the same 4 layers at M={Ms} tokens "
-                                            f"({sec * 1e3:.1f} ms per pass), all channels, all groups"}
+                                  "sample": f"{reps} passes of {'the same 4 layers' if len(layers) == 4 else 'the 4 layers of the first block'} "
+                                            f"at M={Ms} tokens ({sec * 1e3:.1f} ms per pass), all channels, all groups"}
         log(f"[bench] cpu oracle: {val:.3g} {result['unit']} on {ref.num_threads()} threads")
 
     print(json.dumps(result), flush=True)

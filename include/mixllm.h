@@ -102,8 +102,12 @@ typedef struct mixllm_desc {
 typedef struct mixllm_sizes {
     size_t w8_bytes, w4_bytes, scales8_bytes, scales4_bytes, zeros4_bytes, perm_bytes;
     size_t xq_bytes, xscale_bytes, y_bytes;
-    size_t workspace_bytes;   /* scratch for mixllm_mixed_linear_fp16 (xq, then xscale, each rounded up to
-                                 256 B); mixllm_mixed_linear itself needs none */
+    size_t workspace_bytes;   /* scratch mixllm_mixed_linear_fp16 makes use of: xq, then xscale (each rounded up to
+                                 256 B), then linear_workspace_bytes.  It runs with as little as the first two. */
+    size_t linear_workspace_bytes; /* optional scratch of mixllm_mixed_linear: where the tiled path has too few output
+                                 tiles to fill the chip (a few hundred tokens, or few channels) it splits K over several
+                                 blocks and adds their fp32 sums, in a fixed order, from this area; 0 for shapes it
+                                 does not split.  Without it the same kernel runs unsplit. */
 } mixllm_sizes;
 
 const char *mixllm_status_string(int status);
@@ -181,8 +185,11 @@ int mixllm_quantize_activations(const mixllm_desc *d, const void *x, int8_t *xq,
  * The quantized linear (Fig. 1; Sec. 3.3 two-step dequantization; Sec. 3.4 scatter):
  *   P[m,j,g]  = sum_{k in group g} xq[m,k] * (q4[j,k] - z[j,g])   (int32, exact; 8-bit rows: q8)
  *   y[m, feature_perm[j]] = fp16( sum_g float(P[m,j,g]) * s_w[j,g] * s_a[m,g] )   (fp32 sums)
- * One launch covers both parts.  M = 0 is a no-op.  workspace is not used by this call
- * (NULL and 0 are fine); the parameters are kept for callers that size one buffer for all calls.
+ * One launch covers both parts (plus a second, small one where K is split, see below).  M = 0 is a
+ * no-op.  workspace is optional (NULL and 0 are fine): with mixllm_query_sizes().linear_workspace_bytes
+ * of it (16-byte aligned) the tiled path splits K over several blocks where its grid of output tiles
+ * would leave most of the chip idle; with less it splits as far as the bytes reach, or not at all.
+ * The split changes the order of the fp32 additions, nothing else.
  * Errors: EINVAL, EUNSUPPORTED (path cannot run this shape, e.g. DECODE with M > 16),
  * EWORKSPACE, EHIP.
  */
@@ -211,10 +218,13 @@ int mixllm_mixed_linear_fp16(const mixllm_desc *d, const void *x, const void *pa
 /*
  * mixllm_mixed_linear_fp16 for callers that can neither allocate device memory nor hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
- * Same arguments without the workspace, same kernels, same results; the scratch area (xq, xscale)
- * is a device array inside the library, MIXLLM_STATIC_SCRATCH_BYTES long, that every GPU the
- * library runs on holds until the process ends.  The call allocates nothing.
- *   - A shape whose scratch (mixllm_query_sizes().workspace_bytes) exceeds the array is refused
+ * Same arguments without the workspace, same kernels; the scratch area (xq, xscale, then whatever is
+ * left for the tiled path's K split) is a device array inside the library,
+ * MIXLLM_STATIC_SCRATCH_BYTES long, that every GPU the library runs on holds until the process
+ * ends.  The call allocates nothing.  Results are those of mixllm_mixed_linear_fp16 with a
+ * workspace of that size: bit-identical where both have room for the same K split (always when
+ * K < 8192), otherwise the fp32 additions may come in another order.
+ *   - A shape whose xq and xscale (each rounded up to 256 bytes) exceed the array is refused
  *     with MIXLLM_EWORKSPACE before anything is enqueued.  8 MiB + 256 KiB covers M K up to
  *     8 Mi activation values, e.g. 2048 tokens of K = 4096 with either scale granularity.
  *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different
@@ -286,9 +296,10 @@ int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream);
  * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS;
  * path = MIXLLM_PATH_MID: plan[0..4] = blocks of the 8-bit part, of the 4-bit part, quarter tiles
  * per virtual tile of the 8-bit and of the 4-bit part, bytes of LDS; path = MIXLLM_PATH_PREFILL:
- * plan[0..7] = token rows and channels of a block tile, token tiles, channel tiles of the 8-bit and
- * of the 4-bit part, blocks launched, token tiles per band of the block order, bytes of LDS.  plan
- * must hold 8 ints.  Returns EUNSUPPORTED when the path does not cover the shape, EINVAL for other
+ * plan[0..9] = token rows and channels of a block tile, token tiles, channel tiles of the 8-bit and
+ * of the 4-bit part, blocks launched per K part, token tiles per band of the block order, bytes of LDS,
+ * K parts (with linear_workspace_bytes of scratch), quantization groups per K part.  plan must hold
+ * 16 ints.  Returns EUNSUPPORTED when the path does not cover the shape, EINVAL for other
  * paths.
  */
 int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan);

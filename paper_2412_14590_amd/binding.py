@@ -35,7 +35,7 @@ class _Desc(C.Structure):
 class _Sizes(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("w8_bytes", "w4_bytes", "scales8_bytes", "scales4_bytes",
                                           "zeros4_bytes", "perm_bytes", "xq_bytes", "xscale_bytes",
-                                          "y_bytes", "workspace_bytes")]
+                                          "y_bytes", "workspace_bytes", "linear_workspace_bytes")]
 
 
 _lib = None
@@ -226,15 +226,17 @@ def quantize_activations(x: torch.Tensor, act_group=None, out=None):
     return xq, xs
 
 
-def mixed_linear(xq: torch.Tensor, xs: torch.Tensor, L: PackedLayer, path: int = PATH_AUTO, out=None):
-    """The quantized linear: (xq, xscale, packed layer) -> y fp16 [M,N] in original channel order."""
+def mixed_linear(xq: torch.Tensor, xs: torch.Tensor, L: PackedLayer, path: int = PATH_AUTO, out=None, workspace=None):
+    """The quantized linear: (xq, xscale, packed layer) -> y fp16 [M,N] in original channel order.
+    `workspace` (optional uint8 tensor, query_sizes()['linear_workspace_bytes']) lets the tiled path split K."""
     M, K = xq.shape
     assert K == L.K and xs.shape[0] == M
     act_group = K // xs.shape[1]
     y = torch.empty((M, L.N), dtype=torch.float16, device=xq.device) if out is None else out
     d = L.desc(M, act_group)
+    wb = 0 if workspace is None else workspace.numel()
     _check(lib().mixllm_mixed_linear_path(C.byref(d), _ptr(xq), _ptr(xs), _ptr(L.w4), _ptr(L.w8), _ptr(L.s4),
-                                          _ptr(L.s8), _ptr(L.z4), _ptr(L.perm), _ptr(y), None, 0, path,
+                                          _ptr(L.s8), _ptr(L.z4), _ptr(L.perm), _ptr(y), _ptr(workspace), wb, path,
                                           _stream()), "mixllm_mixed_linear")
     return y
 

@@ -48,6 +48,7 @@ void sizes_of(const mixllm_desc &d, mixllm_sizes &s)
     s.xq_bytes = (size_t)d.M * (size_t)d.K;
     s.xscale_bytes = (size_t)d.M * (size_t)(d.K / d.act_group) * 2;
     s.y_bytes = (size_t)d.M * (size_t)d.N * 2;
+    s.linear_workspace_bytes = 0;   // filled in by sizes_with_scratch (needs the launch parameters)
     // scratch of mixllm_mixed_linear_fp16 when it cannot quantize inside the linear kernel: xq, then xscale
     s.workspace_bytes = (size_t)round_up_sz(s.xq_bytes, 256) + (size_t)round_up_sz(s.xscale_bytes, 256);
 }
@@ -78,7 +79,28 @@ LinearParams make_params(const mixllm_desc &d, const int8_t *xq, const void *xsc
     p.perm = perm;
     p.variant = DECODE_ANY;
     p.prefill_tm = 0;
+    p.kparts = 1;
+    p.quads_per_part = (p.ng + 3) / 4;
+    p.np = (p.ntiles8 + p.ntiles4) * TILE_N;
+    p.partials = nullptr;
+    p.partials_cap = 0;
     return p;
+}
+
+// scratch the linear would like for this shape: only the tiled kernel uses any (K split over blocks)
+size_t linear_scratch_bytes(const mixllm_desc &d)
+{
+    if (d.M <= 16) return 0;
+    LinearParams p = make_params(d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    return prefill_scratch_bytes(p);   // (what the tiled kernel would use if the call reaches it)
+}
+
+// sizes_of plus the scratch of the linear; workspace_bytes = xq, xscale, then that scratch
+void sizes_with_scratch(const mixllm_desc &d, mixllm_sizes &s)
+{
+    sizes_of(d, s);
+    s.linear_workspace_bytes = linear_scratch_bytes(d);
+    s.workspace_bytes += s.linear_workspace_bytes;
 }
 
 }  // namespace
@@ -129,14 +151,29 @@ namespace {
 
 int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 
+// The library's choice of kernel.  Up to 16 tokens the decode path.  17 to 64 tokens lie between the
+// two paths the workload names: up to 32 the weight-streaming kernel for a few dozen tokens is the
+// faster one, from 33 on the tiled kernel with its small block shapes (measured on the Llama-shaped
+// layers at 64 tokens: 13 against 16 us, 24 against 26 us, 69 against 80 us) - except on layers
+// with a long K, where the tiled kernel's serial K loop needs the caller's scratch to split K: with
+// it the tiled kernel wins from 17 tokens on (K = 14336: 22 against 28 us at 32 tokens, 23 against
+// 37 us at 64), without it the streaming kernel does.
+int auto_path(const mixllm_desc &d, const LinearParams &p)
+{
+    if (d.M <= 16) return MIXLLM_PATH_DECODE;
+    if (d.M > 64 || !mid_covers(p)) return MIXLLM_PATH_PREFILL;
+    const bool split = prefill_would_split(p);
+    if (d.M <= 32) return (split && p.ng > 64) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
+    return (p.ng < 64 || split) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
+}
+
 // Which kernel a call takes: the caller's path argument with AUTO resolved, or a negative status
 // when that path does not cover the shape.  Host arithmetic only; nothing is launched, so that a
 // call can refuse before it has enqueued anything.  `q` receives the parameters the launch uses.
 int resolve_path(const mixllm_desc &d, const LinearParams &p, int path, LinearParams &q)
 {
     q = p;
-    if (path == MIXLLM_PATH_AUTO)
-        path = d.M <= 16 ? MIXLLM_PATH_DECODE : (d.M <= 64 && mid_covers(p)) ? MIXLLM_PATH_MID : MIXLLM_PATH_PREFILL;
+    if (path == MIXLLM_PATH_AUTO) path = auto_path(d, p);
     const bool sums = p.S != nullptr;   // the sums over the groups come from the generic and the tiled kernel only
     switch (path) {
     case MIXLLM_PATH_GENERIC:
@@ -202,7 +239,7 @@ int mixllm_query_sizes(const mixllm_desc *d, mixllm_sizes *out)
 {
     if (!out) return MIXLLM_EINVAL;
     if (int rc = check_desc(d)) return rc;
-    sizes_of(*d, *out);
+    sizes_with_scratch(*d, *out);
     return MIXLLM_OK;
 }
 
@@ -296,7 +333,7 @@ int mixllm_quantize_activations(const mixllm_desc *d, const void *x, int8_t *xq,
 static int linear_common(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
                          const void *packed_w8, const void *scales4, const void *scales8,
                          const void *zeros4, const int32_t *feature_perm, void *y, int32_t *P, int32_t *S,
-                         int path, void *stream)
+                         int path, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (int rc = check_desc(d)) return rc;
     if (path < MIXLLM_PATH_AUTO || path > MIXLLM_PATH_PREFILL_128) return MIXLLM_EINVAL;
@@ -314,6 +351,12 @@ static int linear_common(const mixllm_desc *d, const int8_t *xq, const void *xsc
     p.y = (half_t *)y;
     p.P = P;
     p.S = S;
+    // optional scratch: the tiled kernel splits K over several blocks where the grid is small, if the
+    // caller brought room for the parts' sums; without it the same kernel runs unsplit
+    if (y && workspace && aligned16(workspace)) {
+        p.partials = (float *)workspace;
+        p.partials_cap = workspace_bytes;
+    }
     return dispatch(*d, p, path, (hipStream_t)stream);
 }
 
@@ -322,10 +365,8 @@ int mixllm_mixed_linear_path(const mixllm_desc *d, const int8_t *xq, const void 
                              const void *scales8, const void *zeros4, const int32_t *feature_perm, void *y,
                              void *workspace, size_t workspace_bytes, int path, void *stream)
 {
-    (void)workspace;   // no kernel of the linear needs scratch memory
-    (void)workspace_bytes;
     return linear_common(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, y,
-                         nullptr, nullptr, path, stream);
+                         nullptr, nullptr, path, workspace, workspace_bytes, stream);
 }
 
 int mixllm_mixed_linear(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
@@ -365,11 +406,17 @@ static int linear_from_fp16(const mixllm_desc *d, const void *x, const void *pac
     // two kernels: the stand-alone quantizer into the scratch area, then the linear; the kernel of the
     // linear is chosen, and the call refused if none takes the shape, before the quantizer is enqueued
     if (!scratch || !aligned16(scratch)) return MIXLLM_EINVAL;
-    if (scratch_bytes < s.workspace_bytes) return MIXLLM_EWORKSPACE;
+    const size_t quant_bytes = round_up_sz(s.xq_bytes, 256) + round_up_sz(s.xscale_bytes, 256);
+    if (scratch_bytes < quant_bytes) return MIXLLM_EWORKSPACE;
     int8_t *xq = (int8_t *)scratch;
     void *xscale = (uint8_t *)scratch + round_up_sz(s.xq_bytes, 256);
     p.xq = xq;
     p.xscale = (const half_t *)xscale;
+    // what is left of the scratch area serves the tiled kernel's K split, if it is enough for that
+    if (scratch_bytes > quant_bytes) {
+        p.partials = (float *)((uint8_t *)scratch + quant_bytes);
+        p.partials_cap = scratch_bytes - quant_bytes;
+    }
     LinearParams q;
     const int path = resolve_path(*d, p, MIXLLM_PATH_AUTO, q);
     if (path < 0) return path;
@@ -423,7 +470,7 @@ int mixllm_mixed_linear_fp16_static(const mixllm_desc *d, const void *x, const v
     // refused before anything is looked up or enqueued; a shape that runs as one kernel does not
     // touch the array, but the limit is the same for every call so that it does not depend on
     // which kernel the library happens to choose
-    if (s.workspace_bytes > (size_t)MIXLLM_STATIC_SCRATCH_BYTES) return MIXLLM_EWORKSPACE;
+    if (round_up_sz(s.xq_bytes, 256) + round_up_sz(s.xscale_bytes, 256) > (size_t)MIXLLM_STATIC_SCRATCH_BYTES) return MIXLLM_EWORKSPACE;
     hipError_t e = hipSuccess;
     void *area = static_scratch_ptr(&e);
     if (!area) return MIXLLM_EHIP;
@@ -472,14 +519,14 @@ int mixllm_debug_work_split(const mixllm_desc *d, int path, int32_t *plan)
     if (int rc = check_desc(d)) return rc;
     if (!plan) return MIXLLM_EINVAL;
     LinearParams p = make_params(*d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-    int out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int out[16] = {0};
     bool ok;
     if (path == MIXLLM_PATH_DECODE_SPLIT) ok = decode_split_plan(p, out);
     else if (path == MIXLLM_PATH_MID) ok = mid_plan(p, out);
     else if (path == MIXLLM_PATH_PREFILL) ok = prefill_plan(p, out);
     else return MIXLLM_EINVAL;
     if (!ok) return MIXLLM_EUNSUPPORTED;
-    for (int i = 0; i < 8; ++i) plan[i] = out[i];
+    for (int i = 0; i < 16; ++i) plan[i] = out[i];
     return MIXLLM_OK;
 }
 
@@ -489,7 +536,7 @@ int mixllm_debug_group_partials(const mixllm_desc *d, const int8_t *xq, const vo
 {
     if (!P) return MIXLLM_EINVAL;
     return linear_common(d, xq, nullptr, packed_w4, packed_w8, nullptr, nullptr, zeros4, feature_perm,
-                         nullptr, P, nullptr, path, stream);
+                         nullptr, P, nullptr, path, nullptr, 0, stream);
 }
 
 int mixllm_debug_channel_sums(const mixllm_desc *d, const int8_t *xq, const void *xscale, const void *packed_w4,
@@ -498,7 +545,7 @@ int mixllm_debug_channel_sums(const mixllm_desc *d, const int8_t *xq, const void
 {
     if (!S) return MIXLLM_EINVAL;
     return linear_common(d, xq, xscale, packed_w4, packed_w8, scales4, scales8, zeros4, feature_perm, nullptr,
-                         nullptr, S, path, stream);
+                         nullptr, S, path, nullptr, 0, stream);
 }
 
 }  // extern "C"

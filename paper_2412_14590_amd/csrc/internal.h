@@ -33,6 +33,12 @@ struct LinearParams {
     int w8_per_channel;  // 1: scales8 [n8p], 0: scales8 [n8p][ngp]
     int variant;         // decode variant requested by the caller's path argument (DECODE_ANY = library's choice)
     int prefill_tm;      // token tiles of 32 per wave of the tiled kernel requested by the caller's path argument (0 = library's choice)
+    // tiled kernel with K split over several blocks: fp32 sums of every part in caller-provided scratch
+    int kparts;          // blocks that share the K range of one output tile (1 = no split)
+    int quads_per_part;  // groups of 4 quantization groups per part
+    int np;              // row stride of `partials`: ntiles8 * 16 + ntiles4 * 16 (the concatenated rows, each part padded)
+    float *partials;     // [kparts][M][np], or null when the caller brought no scratch
+    size_t partials_cap; // bytes behind `partials`: the launcher splits K only as far as they reach
     const half_t *x;   // fp16 activations [M][K]: set only by the fused quantize + linear entry point
     const int8_t *xq;
     const half_t *xscale;
@@ -157,7 +163,11 @@ int cu_count();
 bool decode_can_fuse_quantizer(const LinearParams &p);
 int launch_linear_prefill(const LinearParams &p, hipStream_t st);
 bool prefill_covers(const LinearParams &p);
-bool prefill_plan(const LinearParams &p, int out[8]);
+// scratch bytes the tiled kernel would like for `p` (0 where it does not split K)
+size_t prefill_scratch_bytes(const LinearParams &p);
+// true when the tiled kernel, given p.partials / p.partials_cap, would split K for `p`
+bool prefill_would_split(const LinearParams &p);
+bool prefill_plan(const LinearParams &p, int out[10]);
 // path for 17..128 tokens (linear_mid.hip)
 bool mid_covers(const LinearParams &p);
 int launch_linear_mid(const LinearParams &p, hipStream_t st);

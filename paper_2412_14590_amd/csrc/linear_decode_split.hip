@@ -19,9 +19,10 @@
 //    tile: 4 KB of 4-bit or 8 KB of 8-bit weights) and wave w takes chunks w, w + 8, w + 16,
 //    ... of the share: the eight waves read eight consecutive chunks at a time and end within
 //    one chunk of each other;
-//  * a wave keeps a ring of D chunk requests in flight.  The loads are issued and awaited by
-//    hand (async_loads.h): left to the compiler they are moved next to their first use, and
-//    the ring collapses to one request at a time;
+//  * a wave keeps a ring of chunk requests in flight: two chunks are requested before the block
+//    quantizes and stages its activations, then one beyond the chunk being consumed.  The loads
+//    are issued and awaited by hand (async_loads.h): left to the compiler they are moved next to
+//    their first use, and the ring collapses to one request at a time;
 //  * the int8 activations sit in LDS, staged once per block (with fp16 input of up to 16 Ki
 //    values the block runs the activation quantizer itself, same arithmetic, identical codes);
 //  * the zero point is hoisted out of the unpack, sum a (q - z) = sum a q - z sum a, with
@@ -48,6 +49,12 @@ constexpr int A_PAD = 16;          // bytes added to every staged activation row
 constexpr int LDS_HEADER = 128;    // row maxima of the built-in quantizers in front of the cells
 constexpr int MAX_BLOCKS = 2048;
 constexpr size_t LDS_LIMIT = 156 * 1024;
+#ifndef MIXLLM_SPLIT_RING
+#define MIXLLM_SPLIT_RING 2    // chunks requested before the first is consumed
+#endif
+#ifndef MIXLLM_SPLIT_EARLY
+#define MIXLLM_SPLIT_EARLY 1   // how many of them go out together with the activation loads
+#endif
 
 typedef half_t h8 __attribute__((ext_vector_type(8)));
 
@@ -107,7 +114,13 @@ __device__ inline void await_vec(v4i &a)
 template <int NR, bool DUMP, bool ACT_PT, bool PART8, int FUSED>
 __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, uint8_t *smem)
 {
-    constexpr int D = 2;   // chunk requests in flight per wave, one of them being consumed (measured on 8 to 67 MB layers: every further slot costs 0.3 to 0.7 us)
+    // Chunk requests: R chunks are requested before the first one is consumed - E of them in the
+    // same instant as the activations, the others as soon as the activations have landed, so that
+    // the memory system has work while the block quantizes and stages them - and from then on one
+    // chunk beyond the one being consumed (a ring that stays R deep measured slower: 0.3 to 0.7 us
+    // per slot beyond two on 8 to 67 MB layers).
+    constexpr int R = MIXLLM_SPLIT_RING, E = MIXLLM_SPLIT_EARLY;
+    static_assert(R >= 2 && E >= 1 && E <= R, "ring of at least two slots, at least one early request");
     constexpr int GB = PART8 ? 2048 : 1024;     // bytes of one group of one tile
     constexpr int NLW = PART8 ? 8 : 4;
     constexpr int NLM = PART8 ? (DUMP ? 0 : 1) : (DUMP ? 1 : 2);
@@ -199,8 +212,8 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
         if (j * NT < npiece) load_reg16<0>(xv[j], (uint32_t)min(tid + NT * j, npiece - 1) * 16u, xsrc);
-    Slot<PART8> ring[D];
-    sfor<0, D - 1>([&](auto dc) { issue(decltype(dc)::value, ring[decltype(dc)::value]); });   // always D - 1 chunks (the staging waits count them)
+    Slot<PART8> ring[R];
+    sfor<0, E>([&](auto dc) { issue(decltype(dc)::value, ring[decltype(dc)::value]); });   // always E chunks, past the end of the list dummy ones (the staging waits count them)
     // the output channel and token scales of the first virtual tile this wave will finish:
     // requested now, needed at the very end
     int ch_first = -1;
@@ -228,7 +241,11 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     }
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
-        if (j * NT < npiece) await_vec<(D - 1) * NL>(xv[j]);
+        if (j * NT < npiece) await_vec<E * NL>(xv[j]);
+    sfor<E, R>([&](auto dc) {   // the rest of the first R chunks, where the wave's list has them
+        if (decltype(dc)::value < n_my) issue(decltype(dc)::value, ring[decltype(dc)::value]);
+    });
+    const int primed = max(min(R, n_my), E);   // chunk requests made so far (dummy ones included)
 
     // ---- 2. stage the activations ----
     if (FUSED && !ACT_PT) {
@@ -421,26 +438,28 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
             for (int r = 0; r < NR; ++r) red[((vt * NW + wave) * NR + r) * 64 + lane] += acc[r];
         }
     };
-    for (int i0 = 0; i0 < n_my; i0 += D) {
-        sfor<0, D>([&](auto dc) {
+    for (int i0 = 0; i0 < n_my; i0 += R) {
+        sfor<0, R>([&](auto dc) {
             constexpr int d = decltype(dc)::value;
             const int i = i0 + d;
-            // nothing is requested past the end of the list, so the number of younger loads a
-            // wait may leave in flight shrinks over the last two chunks
-            if (i + D - 1 < n_my) issue(i + D - 1, ring[(d + D - 1) % D]);
             if (i < n_my) {
-                const int younger = min(D - 1, n_my - 1 - i);   // chunks requested after chunk i
-                sfor<0, D>([&](auto yc) {
+                // The first `primed` chunks were requested at the start; from chunk R - 1 on, chunk
+                // i + 1 is requested before chunk i is awaited, into the slot chunk i + 1 - R has
+                // left.  Nothing is requested past the end of the list, so the last wait leaves
+                // nothing in flight.
+                if (i >= R - 1 && i + 1 < n_my) issue(i + 1, ring[(d + 1) % R]);
+                const int younger = i < R - 1 ? primed - 1 - i : (i + 1 < n_my ? 1 : 0);   // chunks requested after chunk i
+                sfor<0, R>([&](auto yc) {
                     constexpr int y = decltype(yc)::value;
                     if (younger == y) await_loads<y * NL>();
                 });
-                await_slot<(D - 1) * NL>(ring[d]);   // ties the registers to the wait above (its own wait is the weakest of them)
+                await_slot<(R - 1) * NL>(ring[d]);   // ties the registers to the wait above (its own wait is the weakest of them)
                 compute(i, ring[d]);
             }
         });
     }
     // nothing may still be on its way into a register when the registers get other uses
-    sfor<0, D>([&](auto dc) { await_slot<0>(ring[decltype(dc)::value]); });
+    sfor<0, R>([&](auto dc) { await_slot<0>(ring[decltype(dc)::value]); });
     if (DUMP) return;
     lds_barrier();
 

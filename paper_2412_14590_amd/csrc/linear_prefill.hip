@@ -26,6 +26,8 @@
 //  * Group metadata (4 fp16 scales, 4 zero points) is fetched once per 4 groups.
 //  * Epilogue: token scale, fp16 conversion, scatter to the original channel (Sec. 3.4).
 // 8-bit and 4-bit channel tiles are different block ranges of one launch.
+#include <algorithm>
+#include <cstdlib>
 #include <mutex>
 #include <type_traits>
 
@@ -35,6 +37,13 @@
 namespace mixllm {
 
 constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
+// groups between the request for packed 4-bit weights and the wait for them, by block shape
+#ifndef MIXLLM_PREFILL_WD_SMALL
+#define MIXLLM_PREFILL_WD_SMALL 2   // 32 x 128 and 64 x 128 blocks
+#endif
+#ifndef MIXLLM_PREFILL_WD_LARGE
+#define MIXLLM_PREFILL_WD_LARGE 1   // 128 x 128 blocks
+#endif
 
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
 template <int I, int N, typename F>
@@ -79,8 +88,11 @@ struct Shape {
 // entry point, the partials are added up in int32 over the groups instead of being rescaled:
 // same arguments, loads, waits, unpack and MFMAs as the linear.
 template <typename C, int DUMP, bool ACT_PT, bool PART8, bool PG8, bool ASYNC>
-static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a, float *lds_sa)
+static __device__ inline void prefill_block(const LinearParams &p, int m0, int t16_0, int g_lo, int g_hi, int kp, uint8_t *lds_a,
+                                            float *lds_sa)
 {
+    // The block walks the quantization groups g_lo .. g_hi - 1 (all of K, or - K split over kparts
+    // blocks - part kp of it; g_lo is a multiple of 4, and so is g_hi unless it is the last group).
     constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG, RING = C::RING;
     constexpr int NSLOT = TM * 4;            // MFMAs per group
     constexpr int NB = C::NB, SB = 4 * NB;   // tiles and MFMA slots of a bundle
@@ -118,7 +130,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     }
     const uint32_t lds_a_wave = __builtin_amdgcn_readfirstlane(lds_address(lds_a) + wave * LPW * 1024);
     auto load_a = [&](int g, int stage) {
-        const int8_t *src = p.xq + (size_t)min(g, ng - 1) * G;
+        const int8_t *src = p.xq + (size_t)min(g, g_hi - 1) * G;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) load_lds16(lds_a_wave + stage * A_STAGE + i * 1024, a_voff[i], src);
     };
@@ -136,12 +148,16 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     v4i b[2][4];
     // packed 4-bit weights are requested WD groups before the wait for them (hand-issued loads
     // only: with ordinary loads the wait below cannot count what is younger in the queue)
-    constexpr int WD = ASYNC ? C::WD : 1, NRAW = 2 * WD;
+    // Raw (packed) weights of groups g + 1 .. g + 1 + WD are live at the middle of group g: WD + 1
+    // ring slots; the slot index is g modulo the ring size, known at compile time only modulo 4
+    // (the K loop is unrolled four groups deep), so the ring has 2 or 4 slots and WD is at most 3.
+    constexpr int WD = ASYNC ? C::WD : 1, NRAW = WD == 1 ? 2 : 4;
+    static_assert(WD >= 1 && WD <= 3, "weight requests run one to three groups ahead");
     constexpr int NMETA = DUMP == 1 ? 1 : 2;   // load instructions load_meta issues for a 4-bit tile in the hand-issued variant
     v4i raw[NRAW][2];
     auto load_b = [&](int g, auto setc) {
         constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW;
-        const int gc = min(g, ng - 1);
+        const int gc = min(g, g_hi - 1);
         if (PART8) {
             const uint8_t *base = (const uint8_t *)p.w8 + (size_t)gc * 2048;
             if (ASYNC) {
@@ -173,7 +189,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     auto load_meta = [&](int q, Meta &mt) {
         mt.s = make_uint2(0, 0);
         mt.z = 0;
-        const int g0 = 4 * min(q, (ng - 1) / 4);
+        const int g0 = 4 * min(q, (g_hi - 1) / 4);
         if (ASYNC) {
             if (PART8) {
                 if (DUMP != 1 && per_group_s8) load_reg8(mt.s, s_voff, p.s8 + g0);
@@ -262,12 +278,12 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
 
     // ---- prologue ------------------------------------------------------------------
     Meta meta_cur, meta_nxt;
-    load_meta(0, meta_cur);
-    load_b(0, std::integral_constant<int, 0>{});
-    if (!PART8) static_for<1, WD + 1>([&](auto gc) { load_b(decltype(gc)::value, gc); });
-    load_a(0, 0);
-    load_a(1, 1);
-    load_a(2, 2);
+    load_meta(g_lo / 4, meta_cur);
+    load_b(g_lo, std::integral_constant<int, 0>{});
+    if (!PART8) static_for<1, WD + 1>([&](auto gc) { load_b(g_lo + decltype(gc)::value, gc); });
+    load_a(g_lo, 0);
+    load_a(g_lo + 1, 1);
+    load_a(g_lo + 2, 2);
     // Activation scale (fp16 bits) of (token row tid, group g+1) on its way to LDS: every thread
     // requests one (rows past the tile re-read its last row), so that all waves count the same loads.
     uint32_t sa_bits = 0;
@@ -277,9 +293,9 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         if (tid < BM) {
 #pragma unroll
             for (int s = 1; s < NSTAGE; ++s) lds_sa[s * BM + tid] = 0.0f;   // read (times a zero scale) before first written
-            lds_sa[tid] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng];
+            lds_sa[tid] = (float)p.xscale[(size_t)min(m0 + tid, p.M - 1) * ng + g_lo];
         }
-        load_reg_u16(sa_bits, sa_voff, p.xscale + min(1, ng - 1));
+        load_reg_u16(sa_bits, sa_voff, p.xscale + min(g_lo + 1, g_hi - 1));
     }
     const float sw_row = (PART8 && DUMP != 1 && !PG8) ? (float)p.s8[rw] : 0.0f;
     // everything above has landed (registers and LDS)
@@ -314,19 +330,19 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     auto group_step = [&](int g, auto uc) {
         constexpr int U = decltype(uc)::value;
         float sw_cur;
-        if (PART8 && !per_group_s8) sw_cur = g < ng ? sw_row : 0.0f;
+        if (PART8 && !per_group_s8) sw_cur = g < g_hi ? sw_row : 0.0f;
         else sw_cur = scale_of(meta_cur, U);   // zero for groups past the end (padding)
         int opaque0 = 0;
         if (DUMP == 1) asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
         uint32_t zb_next = 0;
-        const uint32_t keep_next = g + 1 < ng ? 0xffffffffu : 0u;
+        const uint32_t keep_next = g + 1 < g_hi ? 0xffffffffu : 0u;
         // 8-bit weights need no unpack: group g+1 is requested here, straight into the operand
         // registers group g-1 just vacated; this group's own request (one group old, only the
         // previous middle's activation loads are younger) has to have landed
         if (PART8) {
             await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
             load_b(g + 1, std::integral_constant<int, U + 1>{});
-            if (DUMP == 2 && g >= ng) {
+            if (DUMP == 2 && g >= g_hi) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) b[U % 2][j] = v4i{0, 0, 0, 0};
             }
@@ -355,6 +371,9 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 // that middle's weights and activations, so with per-group activation scales the
                 // WD = 2 wait does not count a metadata request as young.  An 8-bit tile requests
                 // its weights at the start of a group: the 4 loads of group g+1 are the youngest.
+                // (WD >= 2: the wait is bound by group g+1's activations, requested two middles ago,
+                // so the whole batch of the previous middle may stay in flight, however far ahead
+                // the weights run)
                 constexpr int YOUNGER = PART8 ? LPW + 4 : WD == 1 ? LPW : (U == 2 && ACT_PT ? NMETA : 0) + 2 + LPW;
                 if (PART8) await_loads<YOUNGER>();
                 else await_loads<YOUNGER>(raw[(U + 1) % NRAW][0], raw[(U + 1) % NRAW][1]);
@@ -369,7 +388,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 }
                 mid_group_barrier<(!ACT_PT && DUMP != 1)>();
                 if constexpr (U == 1) load_meta(g / 4 + 1, meta_nxt);
-                if (!ACT_PT && DUMP != 1) load_reg_u16(sa_bits, sa_voff, p.xscale + min(g + 2, ng - 1));
+                if (!ACT_PT && DUMP != 1) load_reg_u16(sa_bits, sa_voff, p.xscale + min(g + 2, g_hi - 1));
                 if (!PART8) load_b(g + 1 + WD, std::integral_constant<int, U + 1 + WD>{});
                 load_a(g + 3, (U + 3) % NSTAGE);
                 if (!PART8) zb_next = zbias(((U == 3 ? meta_nxt.z : meta_cur.z) >> (4 * ((U + 1) % 4))) & 15);
@@ -400,14 +419,14 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         });
         sw_prev = sw_cur;
     };
-    for (int g = 0; g < ng; g += 4) {
+    for (int g = g_lo; g < g_hi; g += 4) {
         group_step(g, std::integral_constant<int, 0>{});
         group_step(g + 1, std::integral_constant<int, 1>{});
         group_step(g + 2, std::integral_constant<int, 2>{});
         group_step(g + 3, std::integral_constant<int, 3>{});
         meta_cur = meta_nxt;
     }
-    const int g_last = ((ng + 3) & ~3) - 1;   // group index the pending pair belongs to (may be a phantom one)
+    const int g_last = g_lo + ((g_hi - g_lo + 3) & ~3) - 1;   // group index the pending pair belongs to (may be a phantom one)
     // the last bundle of the last group is still waiting for its rescale
     static_for<0, SB>([&](auto tc) {
         constexpr int t = decltype(tc)::value, j = t / NB, i = t % NB, qp = NBG - 1;
@@ -439,6 +458,20 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         return;
     }
 
+    // ---- K split over several blocks: this block's fp32 sums go to the workspace, in the order of
+    //      the concatenated (padded) rows; prefill_reduce_kernel adds the parts, scales and scatters
+    if (p.kparts > 1) {
+        const int jp = (PART8 ? 0 : p.ntiles8 * TILE_N) + rw;
+        const bool valid = t16 < ntiles;
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < p.M && valid) p.partials[((size_t)kp * p.M + m) * p.np + jp] = acc[mt][r];
+            }
+        return;
+    }
     // ---- epilogue: token scale, fp16, scatter (Sec. 3.4) ------------------------------
     // per token tile: the 16 token scales of the lane's rows are fetched together (clamped,
     // unconditional) so that the loads overlap instead of costing one round trip per row
@@ -465,15 +498,14 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
 // scaled once at the end.  Same activation pipeline as prefill_block; the four token tiles are
 // four independent accumulation chains issued round robin.
 template <typename C, bool ACT_PT, int DUMP>
-static __device__ inline void prefill_block_w8_channel_scale(const LinearParams &p, int m0, int t16_0, uint8_t *lds_a,
-                                                            float *lds_sa)
+static __device__ inline void prefill_block_w8_channel_scale(const LinearParams &p, int m0, int t16_0, int g_lo, int g_hi, int kp,
+                                                            uint8_t *lds_a, float *lds_sa)
 {
     constexpr int TM = C::TM, WN = C::WN, BM = C::BM, A_STAGE = C::A_STAGE, LPW = C::LPW, DFRAG = C::DFRAG, RING = C::RING;
     constexpr int NSLOT = TM * 4, HALF = NSLOT / 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int n32 = lane & 31, h = lane >> 5;
-    const int ng = p.ng;
     const int mw0 = wm * TM * 32;
     const int t16 = t16_0 + wn * 2 + (n32 >> 4);
     const int tile16 = min(t16, p.ntiles8 - 1);
@@ -489,7 +521,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     }
     const uint32_t lds_a_wave = __builtin_amdgcn_readfirstlane(lds_address(lds_a) + wave * LPW * 1024);
     auto load_a = [&](int g, int stage) {
-        const int8_t *src = p.xq + (size_t)min(g, ng - 1) * G;
+        const int8_t *src = p.xq + (size_t)min(g, g_hi - 1) * G;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) load_lds16(lds_a_wave + stage * A_STAGE + i * 1024, a_voff[i], src);
     };
@@ -501,17 +533,17 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     v4i b[2][4];
     auto load_b = [&](int g, auto setc) {
         constexpr int set = decltype(setc)::value % 2;
-        const uint8_t *base = (const uint8_t *)p.w8 + (size_t)min(g, ng - 1) * 2048;
+        const uint8_t *base = (const uint8_t *)p.w8 + (size_t)min(g, g_hi - 1) * 2048;
         load_reg16<0>(b[set][0], b_voff, base);
         load_reg16<512>(b[set][1], b_voff, base);
         load_reg16<1024>(b[set][2], b_voff, base);
         load_reg16<1536>(b[set][3], b_voff, base);
     };
 
-    load_b(0, std::integral_constant<int, 0>{});
-    load_a(0, 0);
-    load_a(1, 1);
-    load_a(2, 2);
+    load_b(g_lo, std::integral_constant<int, 0>{});
+    load_a(g_lo, 0);
+    load_a(g_lo + 1, 1);
+    load_a(g_lo + 2, 2);
     static_assert(ACT_PT, "an integer sum over groups needs an activation scale that does not depend on the group");
     static_assert(DUMP != 1, "one accumulator over all of K: there is no per-group partial to dump");
     const float sw_row = (float)p.s8[rw];
@@ -537,7 +569,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
         // activation loads are younger
         await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
         load_b(g + 1, std::integral_constant<int, U + 1>{});
-        if (g >= ng) {   // a group past the end (K/128 not a multiple of 4) must add nothing
+        if (g >= g_hi) {   // a group past the end (K/128 not a multiple of 4) must add nothing
 #pragma unroll
             for (int j = 0; j < 4; ++j) b[U % 2][j] = v4i{0, 0, 0, 0};
         }
@@ -562,7 +594,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    for (int g = 0; g < ng; g += 4) {
+    for (int g = g_lo; g < g_hi; g += 4) {
         group_step(g, std::integral_constant<int, 0>{});
         group_step(g + 1, std::integral_constant<int, 1>{});
         group_step(g + 2, std::integral_constant<int, 2>{});
@@ -572,6 +604,17 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
     await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
 
+    if (DUMP == 0 && p.kparts > 1) {   // K split over several blocks: see prefill_block
+        const bool valid = t16 < p.ntiles8;
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < p.M && valid) p.partials[((size_t)kp * p.M + m) * p.np + rw] = (float)P[mt][r] * sw_row;
+            }
+        return;
+    }
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
         float sa[16];
@@ -594,6 +637,9 @@ template <typename C, int MINW, int DUMP, bool ACT_PT, bool W8PC>
 __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm, int nb8,
                                                                          int nb4, int per4, int per8, int band)
 {
+    // K split over p.kparts blocks (blockIdx.y): part kp takes 4 * p.quads_per_part groups
+    const int kp = blockIdx.y;
+    const int g_lo = kp * p.quads_per_part * 4, g_hi = min(p.ng, g_lo + p.quads_per_part * 4);
     // dynamic LDS (more than the 64 KB a static array may take): the activation stages, then
     // the per-(token, group) activation scales when they are in use
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -620,11 +666,33 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
     constexpr bool ASYNC = true;   // every variant issues its loads by hand; spill free (checked by the build)
     if (part8) {
         if constexpr (W8PC && ACT_PT && DUMP != 1)
-            prefill_block_w8_channel_scale<C, ACT_PT, DUMP>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+            prefill_block_w8_channel_scale<C, ACT_PT, DUMP>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
         else
-            prefill_block<C, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+            prefill_block<C, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
     } else
-        prefill_block<C, DUMP, ACT_PT, false, false, ASYNC>(p, bm * C::BM, bn * T16, lds_a, lds_sa);
+        prefill_block<C, DUMP, ACT_PT, false, false, ASYNC>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
+}
+
+// K split over several blocks: the parts' fp32 sums (workspace, [part][token][padded concatenated
+// row]) are added in part order - a fixed order, no atomics - scaled by the token's activation
+// scale where that is one per token, converted and scattered (Sec. 3.4).
+__global__ __launch_bounds__(256) void prefill_reduce_kernel(LinearParams p)
+{
+    const int jp = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
+    if (jp >= p.np) return;
+    const int n8p = p.ntiles8 * TILE_N;
+    int j;
+    if (jp < n8p) {
+        if (jp >= p.n8) return;
+        j = jp;
+    } else {
+        if (jp - n8p >= p.n4) return;
+        j = p.n8 + (jp - n8p);
+    }
+    float v = 0.0f;
+    for (int kp = 0; kp < p.kparts; ++kp) v += p.partials[((size_t)kp * p.M + m) * p.np + jp];
+    if (p.act_per_token) v *= (float)p.xscale[m];
+    p.y[(size_t)m * p.N + p.perm[j]] = (half_t)v;
 }
 
 // The kernels take more dynamic LDS than the default limit; raising the limit is a per-function
@@ -656,6 +724,8 @@ static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStre
         }
     }
     hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm, nb8, nb4, per4, per8, band);
+    if (p.kparts > 1)
+        hipLaunchKernelGGL(prefill_reduce_kernel, dim3((p.np + 255) / 256, p.M), dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 
@@ -681,7 +751,7 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
 {
     const PrefillGrid gr = grid_of(p, C::BM, C::BN);
     const int nbm = gr.nbm, nb8 = gr.nb8, nb4 = gr.nb4, per4 = gr.per4, per8 = gr.per8, band = gr.band;
-    dim3 grid((per4 + per8) * 8), block(C::THREADS);
+    dim3 grid((per4 + per8) * 8, p.kparts), block(C::THREADS);
     auto go = [&](auto kernel, bool with_sa) {
         return launch_variant<C>(kernel, with_sa, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
     };
@@ -717,8 +787,8 @@ static int token_tiles_per_wave(const LinearParams &p)
     if (p.prefill_tm) return (p.prefill_tm == 4 && group_scaled_acts) ? 0 : p.prefill_tm;   // the caller's choice (tests, benchmarks)
     const long nbn = (p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
     const long tiles128 = (long)((p.M + 127) / 128) * nbn, tiles64 = (long)((p.M + 63) / 64) * nbn;
-    if (3 * tiles64 <= 2 * cu_count()) return 1;
-    if (3 * tiles128 <= 2 * cu_count() || group_scaled_acts) return 2;
+    if (3 * tiles64 <= 2 * cu_count() || p.M <= 32) return 1;          // (never a block taller than the batch)
+    if (3 * tiles128 <= 2 * cu_count() || group_scaled_acts || p.M <= 64) return 2;
     return 4;
 }
 
@@ -733,10 +803,58 @@ bool prefill_covers(const LinearParams &p)
     return p.M >= 1 && p.N >= 1 && token_tiles_per_wave(p) != 0;
 }
 
-int launch_linear_prefill(const LinearParams &p, hipStream_t st)
+// K split.  A block walks its K range serially, and on layers with a long K (the down projections)
+// that chain, not the chip, sets the time of a launch with few output tiles: 112 groups take 55 us
+// whether 32 or 256 blocks run.  Where the grid of output tiles leaves the chip short of blocks the
+// K range is cut into `kparts` parts for as many blocks (whole groups of 4 quantization groups, at
+// least two of them per part, at most about two blocks per CU in all); the parts' fp32 sums meet in
+// the caller's scratch (prefill_reduce_kernel), which costs a second launch and 8 bytes of traffic
+// per part and output, so it is kept under 12 MB of sums.  Measured (Llama-3-8B down projection,
+// K = 14336, N = 4096): 58 -> 22 us at 32 tokens, 56 -> 23 at 64, 56 -> 34 at 128, 55 -> 46 at
+// 256; Llama-3.1-70B (K = 28672, N = 8192): 124 -> 46 at 32, 119 -> 88 at 128.  With K <= 4096
+// there is nothing to gain (a launch of 32 groups is 7 us of fixed cost plus 0.2 us per group).
+// Returns the number of parts and, in qpp, their length in groups of 4 quantization groups.
+static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &qpp)
 {
-    if (p.M == 0 || p.N == 0) return hipSuccess;
-    if (!prefill_covers(p)) return (int)hipErrorInvalidValue;
+    const int quads = (p.ng + 3) / 4;
+    qpp = quads;
+    if (p.P || p.S || p.ng < 64) return 1;
+    const PrefillGrid g = grid_of(p, 32 * tm, 128);
+    const long blocks = (long)g.nbm * (g.nb8 + g.nb4), slots = 2L * cu_count();
+    const size_t part_bytes = (size_t)p.M * p.np * sizeof(float);
+    long kp = std::min<long>(8, std::min<long>((slots + blocks / 2) / blocks, quads / 2));
+    kp = std::min<long>(kp, (long)(std::min<size_t>(cap_bytes, (size_t)12 << 20) / part_bytes));
+#ifdef MIXLLM_KSPLIT_ENV
+    if (const char *e = getenv("MIXLLM_KPARTS")) kp = std::min<long>(atol(e), std::min<long>(quads, (long)(cap_bytes / part_bytes)));
+#endif
+    if (kp <= 1) return 1;
+    qpp = (int)((quads + kp - 1) / kp);
+    return (quads + qpp - 1) / qpp;   // parts of qpp groups of 4: never more than kp
+}
+
+// true when the kernel, given `p.partials_cap` bytes of scratch, would split K
+bool prefill_would_split(const LinearParams &p)
+{
+    int qpp;
+    return prefill_covers(p) && p.partials && choose_kparts(p, token_tiles_per_wave(p), p.partials_cap, qpp) > 1;
+}
+
+size_t prefill_scratch_bytes(const LinearParams &p)
+{
+    if (!prefill_covers(p)) return 0;
+    int qpp;
+    const int kp = choose_kparts(p, token_tiles_per_wave(p), ~(size_t)0, qpp);
+    return kp > 1 ? (size_t)kp * p.M * p.np * sizeof(float) : 0;
+}
+
+int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
+{
+    if (p0.M == 0 || p0.N == 0) return hipSuccess;
+    if (!prefill_covers(p0)) return (int)hipErrorInvalidValue;
+    LinearParams p = p0;
+    p.kparts = 1;
+    p.quads_per_part = (p.ng + 3) / 4;
+    if (p.partials) p.kparts = choose_kparts(p, token_tiles_per_wave(p), p.partials_cap, p.quads_per_part);
     // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower).
     // Where that grid has clearly less than one block per CU the chip is short of waves, not of rate:
     // blocks of 64 x 128 (wave tile 64 x 32) or 32 x 128 (wave tile 32 x 32) double the waves and
@@ -747,16 +865,16 @@ int launch_linear_prefill(const LinearParams &p, hipStream_t st)
     // 78.0 -> 62.7.  With 192 blocks of 128 x 128 (N = 6144, M = 512) the smaller blocks are 4 % slower,
     // with 224 (N = 28672, M = 128) equal.
     switch (token_tiles_per_wave(p)) {
-    case 1: return launch_shape<Shape<1, 4, 1, 2>, 2>(p, st);
-    case 2: return launch_shape<Shape<1, 4, 2, 2>, 2>(p, st);
-    default: return launch_shape<Shape<1, 4, 4, 1>, 2>(p, st);
+    case 1: return launch_shape<Shape<1, 4, 1, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
+    case 2: return launch_shape<Shape<1, 4, 2, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
+    default: return launch_shape<Shape<1, 4, 4, MIXLLM_PREFILL_WD_LARGE>, 2>(p, st);
     }
 }
 
-// the launch plan as eight integers (token rows and channels of a block tile, token tiles, channel
-// tiles of the 8-bit and of the 4-bit part, blocks launched, token tiles per band, bytes of LDS), for
-// the host-side test of the block -> tile mapping
-bool prefill_plan(const LinearParams &p, int out[8])
+// the launch plan as ten integers (token rows and channels of a block tile, token tiles, channel
+// tiles of the 8-bit and of the 4-bit part, blocks launched per K part, token tiles per band, bytes of
+// LDS, K parts, groups per K part), for the host-side test of the block -> tile mapping
+bool prefill_plan(const LinearParams &p, int out[10])
 {
     if (!prefill_covers(p)) return false;
     const int tm = token_tiles_per_wave(p);
@@ -770,6 +888,9 @@ bool prefill_plan(const LinearParams &p, int out[8])
     out[5] = (g.per4 + g.per8) * 8;
     out[6] = g.band;
     out[7] = NSTAGE * BM * G + ((!p.act_per_token && !p.P) ? NSTAGE * BM * (int)sizeof(float) : 16);   // (p.P is never set here)
+    int qpp;
+    out[8] = choose_kparts(p, tm, ~(size_t)0, qpp);   // blocks sharing a K range when the caller brings the scratch for it
+    out[9] = 4 * qpp;                                 // quantization groups per part
     return true;
 }
 

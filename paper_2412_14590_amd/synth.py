@@ -94,6 +94,14 @@ def select_salient(W: np.ndarray, n8: int, seed: int = 0, n_cal: int = 128) -> n
         return np.zeros(0, np.int32)
     if n8 >= N:
         return np.arange(N, dtype=np.int32)
+    return np.sort(salience_order(W, seed, n_cal)[:n8]).astype(np.int32)
+
+
+def salience_order(W: np.ndarray, seed: int = 0, n_cal: int = 128) -> np.ndarray:
+    """All output channels of W, most salient first, by the modelled 4-bit output error that
+    select_salient describes (equal scores: lower index first).  One ranking serves every 8-bit
+    share of the same weights."""
+    N, K = W.shape
     xc = make_x(n_cal, K, seed, tag="x_cal").astype(np.float32)
     energy = (xc * xc).mean(axis=0).reshape(K // G, G).sum(axis=1)          # [K/G]
     score = np.zeros(N, np.float64)
@@ -102,8 +110,7 @@ def select_salient(W: np.ndarray, n8: int, seed: int = 0, n_cal: int = 128) -> n
         blk = W[r0:r0 + step].astype(np.float32).reshape(-1, K // G, G)
         rng_ = np.maximum(blk.max(axis=2), 0) - np.minimum(blk.min(axis=2), 0)
         score[r0:r0 + step] = (rng_.astype(np.float64) ** 2) @ energy.astype(np.float64)
-    order = np.lexsort((np.arange(N), -score))          # descending score, ties -> lower index
-    return np.sort(order[:n8]).astype(np.int32)
+    return np.lexsort((np.arange(N), -score))           # descending score, ties -> lower index
 
 
 @dataclass

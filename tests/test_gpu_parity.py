@@ -293,6 +293,50 @@ def test_linear_tiled(M, K, N, n8, path, variant):
     check_linear(M, K, N, n8, path, variant)
 
 
+def kparts_of(M, K, N, n8, act_group=None, w8_group=None, path=None):
+    """K parts the tiled kernel uses for this shape when the caller brings the scratch (host-side plan)."""
+    import ctypes as C
+    from paper_2412_14590_amd import binding
+    out = (C.c_int32 * 16)()
+    d = binding._desc(M, K, N, n8, act_group, w8_group)
+    assert mx.lib().mixllm_debug_work_split(C.byref(d), mx.PATH_PREFILL if path is None else path, C.cast(out, C.c_void_p)) == 0
+    return out[8]
+
+
+@pytest.mark.parametrize("variant", ["baseline", "paper", "w8_grouped"])
+@pytest.mark.parametrize("M,K,N,n8", [(33, 8192, 300, 30), (100, 14336, 530, 53), (17, 16384, 96, 96), (64, 8576, 272, 0),
+                                     (256, 28672, 140, 14), (130, 8192, 1030, 103)])
+def test_tiled_path_with_k_split_over_blocks(M, K, N, n8, variant):
+    # Long K, few output tiles: with the scratch mixllm_query_sizes asks for, the tiled kernel cuts K
+    # into parts for several blocks and a second kernel adds the parts' fp32 sums (fixed order).
+    # Against the oracle (row norm and per element), in every block shape, bit-identical between
+    # runs, and through the fp16 entry point; without the scratch the same call runs unsplit.
+    ag, wg = {"baseline": (None, None), "paper": (128, 128), "w8_grouped": (None, 128)}[variant]
+    _, _, L, x, xq, xs = make_case(M, K, N, n8, seed=35, w8_group=wg, act_group=ag)
+    PL = pack_from_oracle(L)
+    need = mx.query_sizes(M, K, N, n8, ag, wg)
+    assert kparts_of(M, K, N, n8, ag, wg) > 1 and need["linear_workspace_bytes"] > 0
+    ws = torch.empty(need["linear_workspace_bytes"], dtype=torch.uint8, device="cuda")
+    y = mx.mixed_linear(dev(xq), dev(xs), PL, mx.PATH_PREFILL, workspace=ws)
+    check_against_oracle(y.cpu().numpy(), xq, xs, L, ("k split", variant, M, K, N, n8))
+    ws.fill_(0xA5)                                         # the kernel may not depend on what the scratch held
+    assert torch.equal(y, mx.mixed_linear(dev(xq), dev(xs), PL, mx.PATH_PREFILL, workspace=ws))
+    for name in ("prefill32", "prefill64", "prefill128"):
+        if name == "prefill128" and variant == "paper":
+            continue
+        big = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        y2 = mx.mixed_linear(dev(xq), dev(xs), PL, PATHS[name], workspace=big)
+        check_against_oracle(y2.cpu().numpy(), xq, xs, L, ("k split", name, variant, M, K, N, n8))
+    y3 = mx.mixed_linear(dev(xq), dev(xs), PL, mx.PATH_PREFILL)        # no scratch: unsplit, same bound
+    check_against_oracle(y3.cpu().numpy(), xq, xs, L, ("no scratch", variant, M, K, N, n8))
+    small = torch.empty(need["linear_workspace_bytes"] // 3 // 16 * 16, dtype=torch.uint8, device="cuda")   # room for fewer parts
+    y4 = mx.mixed_linear(dev(xq), dev(xs), PL, mx.PATH_PREFILL, workspace=small)
+    check_against_oracle(y4.cpu().numpy(), xq, xs, L, ("short scratch", variant, M, K, N, n8))
+    yf = mx.linear_fp16(dev(x), PL, act_group=ag)           # the fp16 entry point brings the same scratch
+    assert torch.equal(yf, y) or M <= 64                    # (up to 64 tokens it may take another kernel)
+    check_against_oracle(yf.cpu().numpy(), xq, xs, L, ("fp16 entry", variant, M, K, N, n8))
+
+
 @pytest.mark.parametrize("M,K,N,n8", [(17, 256, 7, 2), (33, 384, 70, 70), (64, 1024, 530, 0), (50, 640, 50, 5),
                                      (64, 512, 300, 30), (20, 4096, 1000, 100), (64, 14336, 272, 27), (1, 512, 96, 9),
                                      (48, 2048, 2070, 207)])
@@ -455,7 +499,7 @@ def tiled_shape_of(M, lay):
     """The forced-shape path equal to the block shape the tiled kernel picks for this layer at M tokens."""
     import ctypes as C
     from paper_2412_14590_amd import binding
-    out = (C.c_int32 * 8)()
+    out = (C.c_int32 * 16)()
     d = binding._desc(M, lay.K, lay.N, lay.n8)
     assert mx.lib().mixllm_debug_work_split(C.byref(d), mx.PATH_PREFILL, C.cast(out, C.c_void_p)) == 0
     return {32: mx.PATH_PREFILL_32, 64: mx.PATH_PREFILL_64, 128: mx.PATH_PREFILL_128}[out[0]]
@@ -491,8 +535,9 @@ def check_cell(lay, L, PL, M, seed, act_group=None):
     assert np.array_equal(Sg.cpu().numpy()[rows].astype(np.int64), P_ref.sum(axis=2, dtype=np.int64)), tag
     del S, Sg
     yg = mx.mixed_linear(xq, xs, PL, mx.PATH_GENERIC).float()
-    yt = mx.mixed_linear(xq, xs, PL).float()
-    assert torch.equal(yt.half(), y), tag        # the fp16 entry point is quantizer + this launch
+    lws = mx.query_sizes(M, lay.K, lay.N, lay.n8, act_group, PL.w8_group)["linear_workspace_bytes"]
+    yt = mx.mixed_linear(xq, xs, PL, workspace=torch.empty(max(lws, 16), dtype=torch.uint8, device="cuda")).float()
+    assert torch.equal(yt.half(), y), tag        # the fp16 entry point is quantizer + this launch (K split the same way)
     rms = yg.pow(2).mean(dim=1, keepdim=True).sqrt()
     # both kernels round the same fp32-accurate value to fp16: one unit in the last place apart at
     # most, plus their accumulation errors (a few 1e-5 of the row's typical magnitude)

@@ -17,7 +17,7 @@ NW = 8
 
 
 def plan(path, M, K, N, n8):
-    out = (C.c_int32 * 8)()
+    out = (C.c_int32 * 16)()
     d = binding._desc(M, K, N, n8)
     rc = mx.lib().mixllm_debug_work_split(C.byref(d), path, C.cast(out, C.c_void_p))
     return rc, list(out)
@@ -128,12 +128,23 @@ def check_prefill_grid(M, K, N, n8, act_group=None):
     logical ids, then of 8-bit ids; ids walk the tile grid in bands of `band` token tiles (channel
     tile outer, token tile inner).  Restated here: every (token tile, channel tile) of either part
     must be taken by exactly one block, and no block may name a tile outside the grid."""
-    out = (C.c_int32 * 8)()
+    out = (C.c_int32 * 16)()
     d = binding._desc(M, K, N, n8, act_group, None)
     rc = mx.lib().mixllm_debug_work_split(C.byref(d), mx.PATH_PREFILL, C.cast(out, C.c_void_p))
     assert rc == 0
-    BM, BN, nbm, nb8, nb4, blocks, band, lds = list(out)
+    BM, BN, nbm, nb8, nb4, blocks, band, lds, kparts, groups_per_part = list(out)[:10]
     t8, t4 = tiles(N, n8)
+    # K split over blocks (when the caller brings the scratch): whole groups of 4 quantization groups per
+    # part, the parts cover K exactly, no part is empty; only layers with a long K are split, into at
+    # most about two blocks per CU in all, and the parts' sums stay under 12 MB
+    ng = K // 128
+    assert 1 <= kparts <= 8 and groups_per_part % 4 == 0
+    assert (kparts - 1) * groups_per_part < ng <= kparts * groups_per_part
+    if kparts > 1:
+        ntile = nbm * (nb8 + nb4)
+        assert ng >= 64 and groups_per_part >= 8 and ntile * kparts <= 2 * 256 + ntile // 2
+        assert kparts * M * (t8 + t4) * 16 * 4 <= 12 << 20
+    assert BM <= 32 or M > 32
     assert BM in (32, 64, 128) and BN == 128
     assert nbm == -(-M // BM) and nb8 == -(-t8 * 16 // BN) and nb4 == -(-t4 * 16 // BN)
     assert 1 <= band <= min(4, nbm) and lds <= 80 * 1024 and blocks % 8 == 0
