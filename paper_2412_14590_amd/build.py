@@ -153,5 +153,38 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_sanitized_host(driver_cpp: str, exe: str) -> str:
+    """Link `driver_cpp` with the library's sources compiled so that their HOST code carries
+    AddressSanitizer and UndefinedBehaviorSanitizer (device code is compiled as always; the GPU
+    sanitizers are not used).  For the CPU test that runs the host-side validation, size accounting
+    and launch planning under the sanitizers."""
+    objdir = os.path.join(HERE, "_build", "san")
+    os.makedirs(objdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    procs, objs = [], []
+    for src in SOURCES:
+        s, o = os.path.join(CSRC, src), os.path.join(objdir, src.replace(".hip", ".o"))
+        objs.append(o)
+        if not os.path.exists(o) or os.path.getmtime(o) < max(os.path.getmtime(p) for p in (s, os.path.join(CSRC, "internal.h"),
+                                                                                          os.path.join(CSRC, "async_loads.h"),
+                                                                                          os.path.join(INCLUDE, "mixllm.h"), __file__)):
+            procs.append((src, subprocess.Popen([_hipcc(), *FLAGS, *san, "-c", s, "-o", o], stdout=subprocess.PIPE,
+                                                stderr=subprocess.STDOUT, text=True)))
+    for src, pr in procs:
+        out, _ = pr.communicate()
+        if pr.returncode != 0:
+            raise RuntimeError(f"hipcc (host sanitizers) failed on {src}:\n{out}")
+    clang = "/opt/rocm/lib/llvm/bin/clang++"
+    drv = os.path.join(objdir, "driver.o")
+    san_host = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]
+    for cmd in ([clang, "-std=c++17", "-O1", *san_host, "-I", INCLUDE, "-c", driver_cpp, "-o", drv],
+                [_hipcc(), "--offload-arch=gfx950", "-fno-gpu-sanitize", *san_host, "-o", exe, drv, *objs]):
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"{' '.join(cmd[:3])} ... failed:\n{r.stdout}")
+    return exe
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv, verbose=True))
