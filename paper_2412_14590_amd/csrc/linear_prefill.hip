@@ -37,12 +37,26 @@
 namespace mixllm {
 
 constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
-// groups between the request for packed 4-bit weights and the wait for them, by block shape
+// Launch constants, each settable at build time for measurements (the values are the measured best):
+// groups between the request for packed 4-bit weights and the wait for them, by block shape.  One,
+// two or three groups ahead measure the same on every Llama-shaped layer from 64 to 2048 tokens
+// (the wait in the middle of a group is bound by the activations, not by the weights).
 #ifndef MIXLLM_PREFILL_WD_SMALL
 #define MIXLLM_PREFILL_WD_SMALL 2   // 32 x 128 and 64 x 128 blocks
 #endif
 #ifndef MIXLLM_PREFILL_WD_LARGE
 #define MIXLLM_PREFILL_WD_LARGE 1   // 128 x 128 blocks
+#endif
+// token tiles per band of the block order: 4, 8 and 16 measure within 2 % of each other
+#ifndef MIXLLM_PREFILL_BAND
+#define MIXLLM_PREFILL_BAND 4
+#endif
+// waves (32 channels each) of the block with 128 token rows.  With 8 (blocks of 128 x 256, one per
+// CU, half the activation traffic through the L2s) the gate+up layer at 2048 tokens takes the same
+// time (339 against 338 us) and the layers of N <= 6144 up to 20 % longer (fewer, coarser blocks):
+// the kernel is not bound by its L2 traffic.
+#ifndef MIXLLM_PREFILL_WN_LARGE
+#define MIXLLM_PREFILL_WN_LARGE 4
 #endif
 
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
@@ -742,7 +756,7 @@ static PrefillGrid grid_of(const LinearParams &p, int BM, int BN)
     g.nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
     g.per4 = (g.nbm * g.nb4 + 7) / 8;
     g.per8 = (g.nbm * g.nb8 + 7) / 8;
-    g.band = min(4, g.nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
+    g.band = min(MIXLLM_PREFILL_BAND, g.nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
     return g;
 }
 
@@ -819,7 +833,7 @@ static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &q
     const int quads = (p.ng + 3) / 4;
     qpp = quads;
     if (p.P || p.S || p.ng < 64) return 1;
-    const PrefillGrid g = grid_of(p, 32 * tm, 128);
+    const PrefillGrid g = grid_of(p, 32 * tm, tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128);
     const long blocks = (long)g.nbm * (g.nb8 + g.nb4), slots = 2L * cu_count();
     const size_t part_bytes = (size_t)p.M * p.np * sizeof(float);
     long kp = std::min<long>(8, std::min<long>((slots + blocks / 2) / blocks, quads / 2));
@@ -867,7 +881,7 @@ int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
     switch (token_tiles_per_wave(p)) {
     case 1: return launch_shape<Shape<1, 4, 1, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
     case 2: return launch_shape<Shape<1, 4, 2, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
-    default: return launch_shape<Shape<1, 4, 4, MIXLLM_PREFILL_WD_LARGE>, 2>(p, st);
+    default: return launch_shape<Shape<1, MIXLLM_PREFILL_WN_LARGE, 4, MIXLLM_PREFILL_WD_LARGE>, 2>(p, st);
     }
 }
 
@@ -878,7 +892,7 @@ bool prefill_plan(const LinearParams &p, int out[10])
 {
     if (!prefill_covers(p)) return false;
     const int tm = token_tiles_per_wave(p);
-    const int BM = 32 * tm, BN = 128;
+    const int BM = 32 * tm, BN = tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128;
     const PrefillGrid g = grid_of(p, BM, BN);
     out[0] = BM;
     out[1] = BN;
