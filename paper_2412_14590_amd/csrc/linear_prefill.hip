@@ -692,21 +692,26 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
 // scale where that is one per token, converted and scattered (Sec. 3.4).
 __global__ __launch_bounds__(256) void prefill_reduce_kernel(LinearParams p)
 {
-    const int jp = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
-    if (jp >= p.np) return;
+    // four consecutive rows of the padded concatenation per thread (p.np is a multiple of 16)
+    const int jp0 = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
+    if (jp0 >= p.np) return;
     const int n8p = p.ntiles8 * TILE_N;
-    int j;
-    if (jp < n8p) {
-        if (jp >= p.n8) return;
-        j = jp;
-    } else {
-        if (jp - n8p >= p.n4) return;
-        j = p.n8 + (jp - n8p);
+    v4f v = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int kp = 0; kp < p.kparts; ++kp) v += *(const v4f *)(p.partials + ((size_t)kp * p.M + m) * p.np + jp0);
+    const float sa = p.act_per_token ? (float)p.xscale[m] : 1.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int jp = jp0 + i;
+        int j;
+        if (jp < n8p) {
+            if (jp >= p.n8) continue;
+            j = jp;
+        } else {
+            if (jp - n8p >= p.n4) continue;
+            j = p.n8 + (jp - n8p);
+        }
+        p.y[(size_t)m * p.N + p.perm[j]] = (half_t)(v[i] * sa);
     }
-    float v = 0.0f;
-    for (int kp = 0; kp < p.kparts; ++kp) v += p.partials[((size_t)kp * p.M + m) * p.np + jp];
-    if (p.act_per_token) v *= (float)p.xscale[m];
-    p.y[(size_t)m * p.N + p.perm[j]] = (half_t)v;
 }
 
 // The kernels take more dynamic LDS than the default limit; raising the limit is a per-function
@@ -739,7 +744,7 @@ static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStre
     }
     hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm, nb8, nb4, per4, per8, band);
     if (p.kparts > 1)
-        hipLaunchKernelGGL(prefill_reduce_kernel, dim3((p.np + 255) / 256, p.M), dim3(256), 0, st, p);
+        hipLaunchKernelGGL(prefill_reduce_kernel, dim3((p.np / 4 + 255) / 256, p.M), dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 
