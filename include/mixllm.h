@@ -57,7 +57,8 @@ enum {
 
 /* Kernel selection for the entry points that take a `path` argument. */
 enum {
-    MIXLLM_PATH_AUTO = 0,    /* decode path for M <= 16, the path for a few dozen tokens up to M = 64, tiled MFMA path otherwise */
+    MIXLLM_PATH_AUTO = 0,    /* decode path for M <= 16; 17..64 tokens: the path for a few dozen tokens or the tiled path,
+                                whichever measured faster for the shape; tiled MFMA path otherwise */
     MIXLLM_PATH_GENERIC = 1, /* one thread per output element, no MFMA; any shape; slow */
     MIXLLM_PATH_DECODE = 2,  /* weight-streaming path, M <= 16; picks one of the three variants below */
     MIXLLM_PATH_PREFILL = 3, /* LDS-staged tiled MFMA path, any M */
@@ -65,7 +66,8 @@ enum {
     MIXLLM_PATH_DECODE_STREAM = 4,   /* a wave per tile (or per K part of a tile), activations re-read per tile */
     MIXLLM_PATH_DECODE_RESIDENT = 5, /* activation fragments kept in registers; falls back to STREAM where it cannot run */
     MIXLLM_PATH_DECODE_SPLIT = 6,    /* equal byte shares per block, activations in LDS; EUNSUPPORTED where it cannot run */
-    MIXLLM_PATH_MID = 7,             /* weight-streaming path for a few dozen tokens, M <= 64; EUNSUPPORTED where it cannot run */
+    MIXLLM_PATH_MID = 7,             /* weight-streaming path for a few dozen tokens, M <= 64 (M <= 32 with one activation
+                                        scale per (token, group)); EUNSUPPORTED where it cannot run */
     /* the tiled path with the block shape chosen by the caller instead of by the grid size, for tests
        and benchmarks: 32, 64 or 128 token rows x 128 channels */
     MIXLLM_PATH_PREFILL_32 = 8,

@@ -19,8 +19,10 @@
 //  * Per group: unpack with the zero point subtracted (step 1 of the two-step dequantization,
 //    Sec. 3.3), MT x 2 `v_mfma_i32_16x16x64_i8`, int32 partial per group, fp32 rescale (step 2).
 //    Token scale, fp16 conversion and scatter (Sec. 3.4) at the end of a round.
-// Covers per-token activation scales and per-channel 8-bit scales (the measured configuration);
-// other shapes take the tiled kernel.
+// Both scale granularities: with one activation scale per (token, group) the scales of the whole
+// batch sit in LDS next to the stages (converted to fp32 once per block) and every group's partial
+// is multiplied by its token's scale of that group; with one 8-bit weight scale per group the 8-bit
+// tiles fetch four fp16 scales per K step like the 4-bit ones.
 #include <algorithm>
 #include <type_traits>
 
@@ -75,14 +77,17 @@ __device__ inline void tie_slot(Slot<true> &k)
 {
     asm volatile(""
                  : "+v"(k.w[0][0]), "+v"(k.w[0][1]), "+v"(k.w[1][0]), "+v"(k.w[1][1]), "+v"(k.w[2][0]), "+v"(k.w[2][1]),
-                   "+v"(k.w[3][0]), "+v"(k.w[3][1])::"memory");
+                   "+v"(k.w[3][0]), "+v"(k.w[3][1]), "+v"(k.s)::"memory");
 }
 
-template <int MT, bool DUMP, bool PART8>
+// ACT_PT: one activation scale per token (else per token and group); W8PC: one scale per 8-bit
+// channel (else per channel and group)
+template <int MT, bool DUMP, bool PART8, bool ACT_PT, bool W8PC>
 __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_t *smem)
 {
     constexpr int GB = PART8 ? 2048 : 1024;    // bytes of one group of one tile
-    constexpr int NL = PART8 ? 8 : 6;          // loads of one K step of weights
+    constexpr bool PG8 = PART8 && !W8PC && !DUMP;   // 8-bit tile that fetches group scales
+    constexpr int NL = PART8 ? (PG8 ? 9 : 8) : 6;   // loads of one K step of weights
     constexpr int MP = MT * 16;                // staged token rows
     constexpr int GROUP_STAGE = MP * G;        // bytes of one group of the activation stage
     constexpr int STAGE = 4 * GROUP_STAGE;
@@ -130,6 +135,11 @@ __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_
     // fragment reads: token row 16 mt + c, 16-byte chunk ks (k 0..63 of the group) and 4 + ks
     const int sw = (c >> 1) & 7;
     const int a_rd0 = c * G + ((ks ^ sw) << 4), a_rd1 = c * G + (((4 + ks) ^ sw) << 4);
+    // activation scales per (token, group): the whole batch, as fp32, behind the stages (visible
+    // after the barrier that opens the first round)
+    float *xsg = (float *)(smem + NBUF * STAGE);
+    if (!ACT_PT && !DUMP)
+        for (int i = tid; i < p.M * ng; i += NT) xsg[i] = (float)p.xscale[i];
 
     const uint8_t *wpart = PART8 ? (const uint8_t *)p.w8 : p.w4;
     for (int r = 0; r < rounds; ++r) {
@@ -147,7 +157,7 @@ __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_
         const uint32_t w_voff = has ? (uint32_t)((rel >> 4) * ng * GB + ((rel & 15) + 16 * ks) * 16) : 0u;
         const uint32_t s_voff = has ? (uint32_t)(rel * ngp * 2) : 0u, z_voff = has ? (uint32_t)(rel * (ngp / 2)) : 0u;
         const int ch = (lane_valid && row < nrows) ? p.perm[joff + row] : -1;
-        const float sw_row = (PART8 && !DUMP) ? (float)p.s8[row] : 0.0f;
+        const float sw_row = (PART8 && W8PC && !DUMP) ? (float)p.s8[row] : 0.0f;
         auto issue = [&](int q, Slot<PART8> &k) {
             const int g0 = 4 * q;
             const int last = ng - 1 - g0;   // at the ragged end of K the last group is re-read (its scale is forced to zero)
@@ -165,6 +175,8 @@ __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_
                 if (!DUMP) load_reg8(k.s, s_voff, p.s4 + ((size_t)base_tile * TILE_N * ngp + g0));
                 else load_reg8(k.s, 0u, p.z4);
                 load_reg_u16(k.z, z_voff, p.z4 + ((size_t)base_tile * TILE_N * (ngp / 2) + g0 / 2));
+            } else if (PG8) {
+                load_reg8(k.s, s_voff, p.s8 + ((size_t)base_tile * TILE_N * ngp + g0));
             }
         };
         float acc[MT][4];
@@ -204,7 +216,7 @@ __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_
                 if (PART8) {
                     b0 = k.w[u][0];
                     b1 = k.w[u][PART8 ? 1 : 0];
-                    swg = sw_row;
+                    swg = PG8 ? sh[u] : sw_row;
                 } else {
                     const uint32_t zb = zbias((int)((k.z >> (4 * u)) & 15));
                     const v4i w = k.w[u][0];
@@ -230,9 +242,16 @@ __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_
                                 if (m < p.M) p.P[((size_t)m * p.N + ch) * ng + g] = P[mt][i];
                             }
                         }
-                    } else {
+                    } else if (ACT_PT) {
 #pragma unroll
                         for (int i = 0; i < 4; ++i) acc[mt][i] = __builtin_fmaf((float)P[mt][i], swg, acc[mt][i]);
+                    } else {
+                        const int gc = min(g, ng - 1);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float sa = xsg[min(mt * 16 + 4 * ks + i, p.M - 1) * ng + gc];
+                            acc[mt][i] = __builtin_fmaf((float)P[mt][i], swg * sa, acc[mt][i]);
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -280,20 +299,20 @@ __device__ inline void mid_block(const LinearParams &p, const MidArgs &a, uint8_
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int m = mt * 16 + 4 * ks + i;
-                    if (m < p.M) p.y[(size_t)m * p.N + ch] = (half_t)(acc[mt][i] * (float)p.xscale[m]);
+                    if (m < p.M) p.y[(size_t)m * p.N + ch] = (half_t)(ACT_PT ? acc[mt][i] * (float)p.xscale[m] : acc[mt][i]);
                 }
         }
     }
 }
 
-template <int MT, bool DUMP>
+template <int MT, bool DUMP, bool ACT_PT, bool W8PC>
 __global__ __launch_bounds__(NT) void linear_mid_kernel(LinearParams p, MidArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     if ((int)blockIdx.x < a.nblk8)
-        mid_block<MT, DUMP, true>(p, a, smem);
+        mid_block<MT, DUMP, true, ACT_PT, W8PC>(p, a, smem);
     else
-        mid_block<MT, DUMP, false>(p, a, smem);
+        mid_block<MT, DUMP, false, ACT_PT, W8PC>(p, a, smem);
 }
 
 // ---- host side ------------------------------------------------------------------------------
@@ -332,13 +351,23 @@ void split_blocks(int units8, int units4, int nb, int &nblk8, int &nblk4)
 
 int token_tiles(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
 
+// the activation stages, then the activation scales of the batch where there is one per (token, group)
+size_t lds_bytes_of(const LinearParams &p)
+{
+    const int mt = token_tiles(p.M);
+    const size_t xsg = (p.act_per_token || p.P) ? 0 : ((size_t)p.M * p.ng * sizeof(float) + 15) / 16 * 16;
+    return (size_t)stage_buffers(mt) * mt * 8 * 1024 + xsg;
+}
+
 }  // namespace
 
 bool mid_covers(const LinearParams &p)
 {
-    if (p.M < 1 || p.M > 64 || p.ng < 1) return false;
-    if (!p.act_per_token || !p.w8_per_channel || p.x) return false;
-    if ((size_t)stage_buffers(token_tiles(p.M)) * token_tiles(p.M) * 8 * 1024 > LDS_LIMIT) return false;
+    if (p.M < 1 || p.M > 64 || p.ng < 1 || p.x) return false;
+    // one activation scale per (token, group): up to 32 tokens (with four token tiles per wave the extra
+    // scale reads do not fit the register file next to the weight ring: the tiled kernel takes those)
+    if (!p.act_per_token && !p.P && p.M > 32) return false;
+    if (lds_bytes_of(p) > LDS_LIMIT) return false;
     // 32-bit lane offsets inside the activation, weight and metadata arrays
     const size_t two_tiles = 2 * (size_t)p.ng * 2048 + 2048;
     if ((size_t)p.M * p.K >= (1ull << 31) || two_tiles >= (1ull << 31)) return false;
@@ -352,8 +381,7 @@ static void mid_args(const LinearParams &p, MidArgs &a, size_t &lds_bytes)
     split_blocks(4 * p.ntiles8, 4 * p.ntiles4, cu_count(), a.nblk8, a.nblk4);
     a.qv8 = a.nblk8 ? pick_qv(ceil_div(4 * p.ntiles8, a.nblk8)) : 4;
     a.qv4 = a.nblk4 ? pick_qv(ceil_div(4 * p.ntiles4, a.nblk4)) : 4;
-    const int mt = token_tiles(p.M);
-    lds_bytes = (size_t)stage_buffers(mt) * mt * 8 * 1024;
+    lds_bytes = lds_bytes_of(p);
 }
 
 // the launch plan as five integers (blocks of the 8-bit part, of the 4-bit part, quarter tiles per
@@ -388,15 +416,22 @@ int launch_linear_mid(const LinearParams &p, hipStream_t st)
     };
     if (p.P) {
         switch (mt) {
-        case 1: return go(linear_mid_kernel<1, true>);
-        case 2: return go(linear_mid_kernel<2, true>);
-        default: return go(linear_mid_kernel<4, true>);
+        case 1: return go(linear_mid_kernel<1, true, true, true>);
+        case 2: return go(linear_mid_kernel<2, true, true, true>);
+        default: return go(linear_mid_kernel<4, true, true, true>);
         }
     }
+    auto pick = [&](auto mtc) {
+        constexpr int MT = decltype(mtc)::value;
+        if (p.act_per_token) return p.w8_per_channel ? go(linear_mid_kernel<MT, false, true, true>) : go(linear_mid_kernel<MT, false, true, false>);
+        if constexpr (MT <= 2)
+            return p.w8_per_channel ? go(linear_mid_kernel<MT, false, false, true>) : go(linear_mid_kernel<MT, false, false, false>);
+        return (int)hipErrorInvalidValue;   // (mid_covers refuses these)
+    };
     switch (mt) {
-    case 1: return go(linear_mid_kernel<1, false>);
-    case 2: return go(linear_mid_kernel<2, false>);
-    default: return go(linear_mid_kernel<4, false>);
+    case 1: return pick(std::integral_constant<int, 1>{});
+    case 2: return pick(std::integral_constant<int, 2>{});
+    default: return pick(std::integral_constant<int, 4>{});
     }
 }
 

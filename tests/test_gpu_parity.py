@@ -341,10 +341,20 @@ def test_tiled_path_with_k_split_over_blocks(M, K, N, n8, variant):
                                      (64, 512, 300, 30), (20, 4096, 1000, 100), (64, 14336, 272, 27), (1, 512, 96, 9),
                                      (48, 2048, 2070, 207)])
 def test_mid_path_partials_and_linear(M, K, N, n8):
-    # the path for a few dozen tokens: integer partials bit-exact, outputs within tolerance
+    # the path for a few dozen tokens: integer partials bit-exact, outputs within tolerance, in every
+    # scale granularity it covers (activation scales per token and group: up to 32 tokens)
     say("mid", M, K, N, n8)
     check_partials(M, K, N, n8, "mid")
     check_linear(M, K, N, n8, "mid")
+    for ag, wg in ((None, 128), (128, None), (128, 128)):
+        _, _, L, _, xq, xs = make_case(M, K, N, n8, 29, wg, ag)
+        if ag == 128 and M > 32:
+            with pytest.raises(mx.MixllmError) as e:
+                mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), mx.PATH_MID)
+            assert e.value.status == -2
+            continue
+        y = mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), mx.PATH_MID)
+        check_against_oracle(y.cpu().numpy(), xq, xs, L, ("mid", ag, wg, M, K, N, n8))
 
 
 def test_mid_path_rejects_what_it_does_not_cover():
@@ -354,7 +364,7 @@ def test_mid_path_rejects_what_it_does_not_cover():
     assert e.value.status == -2
     _, _, L, _, xq, xs = make_case(40, 256, 40, 4, seed=3, w8_group=128, act_group=128)
     with pytest.raises(mx.MixllmError) as e:
-        mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), mx.PATH_MID)       # group-wise scales
+        mx.mixed_linear(dev(xq), dev(xs), pack_from_oracle(L), mx.PATH_MID)       # activation scales per group, more than 32 tokens
     assert e.value.status == -2
 
 
