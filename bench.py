@@ -195,17 +195,96 @@ def share_sweep(args, torch, mx, synth, dev):
             "roofline": ref_row["roofline"], "rows": rows}
 
 
+def shape_sweep(args, torch, mx, synth, dev):
+    """Every layer of a decoder block x token counts x kernel choices: the library's own choice (with
+    and without the optional scratch of the linear), the tiled kernel in each block shape, the kernel
+    for a few dozen tokens, the decode kernel - time of the linear alone, launches replayed from a HIP
+    graph with the weights rotating over >= 512 MB of copies, against min(HBM, int8 MFMA).  This is the
+    measurement behind the dispatch rules (which kernel, which block shape, whether K is split); a
+    library built with other launch constants (MIXLLM_EXTRA_FLAGS / MIXLLM_LIB_OUT of the build,
+    MIXLLM_LIB of the binding) is measured the same way."""
+    Ms = [int(m) for m in args.ms.split(",")]
+    paths = {"auto": mx.PATH_AUTO, "tiled_32x128": mx.PATH_PREFILL_32, "tiled_64x128": mx.PATH_PREFILL_64,
+             "tiled_128x128": mx.PATH_PREFILL_128, "few_dozen_tokens": mx.PATH_MID, "decode": mx.PATH_DECODE}
+
+    def graph_time(fn, reps):
+        for i in range(4):
+            fn(i)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for i in range(reps):
+                    fn(i)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            g.replay()
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b) * 1e-3 / reps)
+        return best
+
+    rows = []
+    for name, K, N, sigma, n_out in synth.model_layers(args.model):
+        W = torch.from_numpy(synth.make_w(N, K, sigma, n_out, seed=0, tag="w/" + name)).to(dev)
+        n8 = synth.n8_for(N, 0.10)
+        L0 = mx.quantize_weights(W, torch.randperm(N, device=dev, generator=torch.Generator(device=dev).manual_seed(1))[:n8].to(torch.int32))
+        del W
+        n_c = max(2, -(-2 * MALL_BYTES // L0.weight_bytes()))
+        Ls = [L0] + [L0.clone() for _ in range(n_c - 1)]
+        for M in Ms:
+            x = torch.from_numpy(synth.make_x(M, K, seed=7, tag="x/" + name)).to(dev)
+            xq, xs = mx.quantize_activations(x)
+            y = torch.empty((M, N), dtype=torch.float16, device=dev)
+            ws = torch.empty(max(16, mx.query_sizes(M, K, N, n8)["linear_workspace_bytes"]), dtype=torch.uint8, device=dev)
+            big = torch.empty(64 << 20, dtype=torch.uint8, device=dev)       # room for any K split of a forced block shape
+            nb, ops = layer_alg_bytes(K, N, n8, M), 2.0 * M * N * K
+            row = {"layer": name, "K": K, "N": N, "n8": n8, "M": M, "us": {}}
+            graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], out=y), 40 if M <= 512 else 20)   # clocks settle before the first figure
+            for pn, pv in paths.items():
+                for scratch in ((None, ws) if pn == "auto" else (big,) if pn.startswith("tiled") else (None,)):
+                    key = pn + ("" if pn != "auto" else "+scratch" if scratch is not None else "")
+                    try:
+                        t = graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], pv, out=y, workspace=scratch), 20 if M <= 512 else 8)
+                    except mx.MixllmError:
+                        continue
+                    row["us"][key] = round(t * 1e6, 1)
+            t_auto = row["us"]["auto+scratch"] * 1e-6
+            row["roofline"] = roofline_entry(nb, ops, t_auto)
+            rows.append(row)
+            log(f"[shapes] {name} K={K} N={N} M={M}: {json.dumps(row['us'])}  auto+scratch {row['roofline']['frac_of_min_hbm_mfma']:.2f} of min(HBM, MFMA)")
+        del Ls, L0
+        torch.cuda.empty_cache()
+    ref_row = max(rows, key=lambda r: (r["K"] * r["N"], -r["M"]))
+    return {"metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)", "value": ref_row["roofline"]["achieved"],
+            "unit": ref_row["roofline"]["unit"], "n_gpus": 1, "steps": 20, "warmup": 4, "ms_per_step": ref_row["us"]["auto+scratch"] * 1e-3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+            "config": {"workload": f"single linears of the {args.model} block, M in {Ms}, every kernel choice; value = the largest layer at the "
+                                   f"smallest M, library's choice", "library": os.environ.get("MIXLLM_LIB", "in-tree build")},
+            "roofline": ref_row["roofline"], "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["decode", "prefill", "70b", "stack", "share-sweep", "salience"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "70b", "stack", "share-sweep", "salience", "shapes"], default="decode",
                     help="decode / prefill: one Llama-3-8B-shaped block at M = 1 / 2048 (plus the other token counts as extra "
                          "legs); 70b: one Llama-3.1-70B-shaped block, M in {1, 16, 64, 256, 2048}; stack: 32 8B-shaped blocks "
                          "back to back with an uneven 8-bit share per layer, M in {1, 256}; share-sweep: single linears "
                          "K=4096, N in {4096, 14336}, 8-bit shares 0..100 %%, M = 1..1024 (the grid of the paper's "
-                         "single-linear study, Sec. 5.2); salience: the global precision search of Sec. 3.2")
+                         "single-linear study, Sec. 5.2); salience: the global precision search of Sec. 3.2; shapes: every "
+                         "layer of a block (--model) x token counts (--ms) x kernel choice, the measurement behind the dispatch rules")
+    ap.add_argument("--model", choices=["8b", "70b"], default="8b", help="layer shapes of --workload shapes")
+    ap.add_argument("--ms", default="32,64,128,256,512", help="token counts of --workload shapes, comma separated")
     ap.add_argument("--m", type=int, default=None, help="tokens of the primary leg (default 1; 2048 for --workload prefill)")
     ap.add_argument("--no-extras", action="store_true", help="primary leg only (for profiling)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
@@ -230,6 +309,9 @@ def main():
         return
     if args.workload == "share-sweep":
         print(json.dumps(share_sweep(args, torch, mx, synth, dev)), flush=True)
+        return
+    if args.workload == "shapes":
+        print(json.dumps(shape_sweep(args, torch, mx, synth, dev)), flush=True)
         return
     M0 = args.m if args.m is not None else (2048 if args.workload == "prefill" else 1)
 

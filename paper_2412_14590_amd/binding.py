@@ -12,7 +12,9 @@ import numpy as np
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libmixllm_hip.so")
+# the in-tree build; MIXLLM_LIB names another build of the same sources (say one made with other launch
+# constants through MIXLLM_EXTRA_FLAGS / MIXLLM_LIB_OUT of the build script, to be measured with bench.py)
+LIB_PATH = os.environ.get("MIXLLM_LIB") or os.path.join(HERE, "libmixllm_hip.so")
 GROUP = 128
 
 PATH_AUTO, PATH_GENERIC, PATH_DECODE, PATH_PREFILL = 0, 1, 2, 3

@@ -100,7 +100,11 @@ def check_hand_issued_loads(asm_text: str, name: str) -> None:
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Objects are cached per source
     by modification time unless force is set."""
-    objdir = os.path.join(HERE, "_build")
+    # a build with extra flags (other launch constants, for measurements) keeps its objects apart from
+    # the default build's and is always compiled afresh
+    variant = bool(os.environ.get("MIXLLM_EXTRA_FLAGS", "").strip())
+    objdir = os.path.join(HERE, "_build", "variant") if variant else os.path.join(HERE, "_build")
+    force = force or variant
     os.makedirs(objdir, exist_ok=True)
     deps = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "async_loads.h"), os.path.join(INCLUDE, "mixllm.h"), __file__]
     dep_m = max(os.path.getmtime(p) for p in deps)
@@ -144,6 +148,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc -S failed for {src}:\n{out}")
         check_hand_issued_loads(open(a).read(), src)
     subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    if variant:
+        return LIB
     # the ceiling probes of the benchmark: a separate small library
     r = subprocess.run([_hipcc(), *FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, "probe.hip")],
                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -153,18 +153,22 @@ int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 
 // The library's choice of kernel.  Up to 16 tokens the decode path.  17 to 64 tokens lie between the
 // two paths the workload names: up to 32 the weight-streaming kernel for a few dozen tokens is the
-// faster one, from 33 on the tiled kernel with its small block shapes (measured on the Llama-shaped
-// layers at 64 tokens: 13 against 16 us, 24 against 26 us, 69 against 80 us) - except on layers
-// with a long K, where the tiled kernel's serial K loop needs the caller's scratch to split K: with
-// it the tiled kernel wins from 17 tokens on (K = 14336: 22 against 28 us at 32 tokens, 23 against
-// 37 us at 64), without it the streaming kernel does.
+// faster one, from 33 on the tiled kernel with its small block shapes (measured at 64 tokens on the
+// Llama-shaped layers: K = N = 4096 13 against 16 us, K = 8192, N = 57344 67 against 81 us, the
+// others within 15 % either way) - except on layers with a long K, where the tiled kernel's serial
+// K loop needs the caller's scratch to split K: with it the tiled kernel wins from 17 tokens on
+// (K = 14336: 23 against 27 us at 32 tokens, 23 against 37 us at 64), without it the streaming
+// kernel does.
 int auto_path(const mixllm_desc &d, const LinearParams &p)
 {
     if (d.M <= 16) return MIXLLM_PATH_DECODE;
     if (d.M > 64 || !mid_covers(p)) return MIXLLM_PATH_PREFILL;
     const bool split = prefill_would_split(p);
     if (d.M <= 32) return (split && p.ng > 64) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
-    return (p.ng < 64 || split) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
+    // 33..64 tokens: the tiled kernel, except where its K loop is long, cannot be split and the grid of
+    // 64 x 128 tiles leaves CUs empty (K = 14336, N = 4096 without scratch: 56 against 37 us)
+    const long tiles = (long)(p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
+    return (p.ng < 64 || split || tiles >= cu_count()) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
 }
 
 // Which kernel a call takes: the caller's path argument with AUTO resolved, or a negative status
