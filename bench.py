@@ -247,12 +247,14 @@ def shape_sweep(args, torch, mx, synth, dev):
             big = torch.empty(64 << 20, dtype=torch.uint8, device=dev)       # room for any K split of a forced block shape
             nb, ops = layer_alg_bytes(K, N, n8, M), 2.0 * M * N * K
             row = {"layer": name, "K": K, "N": N, "n8": n8, "M": M, "us": {}}
-            graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], out=y), 40 if M <= 512 else 20)   # clocks settle before the first figure
+            # a replay walks all n_c copies (>= 512 MB): every launch reads its weights from HBM, as in a step of the model
+            reps = max(20 if M <= 512 else 8, n_c)
+            graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], out=y), reps)   # clocks settle before the first figure
             for pn, pv in paths.items():
                 for scratch in ((None, ws) if pn == "auto" else (big,) if pn.startswith("tiled") else (None,)):
                     key = pn + ("" if pn != "auto" else "+scratch" if scratch is not None else "")
                     try:
-                        t = graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], pv, out=y, workspace=scratch), 20 if M <= 512 else 8)
+                        t = graph_time(lambda i: mx.mixed_linear(xq, xs, Ls[i % n_c], pv, out=y, workspace=scratch), reps)
                     except mx.MixllmError:
                         continue
                     row["us"][key] = round(t * 1e6, 1)
