@@ -153,14 +153,14 @@ int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 
 // The library's choice of kernel.  Up to 16 tokens the decode path.  17 to 64 tokens lie between the
 // two paths the workload names.  Measured with every launch reading its weights from HBM (copies of
-// the layer rotating over 512 MB, as in a step of a model): the tiled kernel walks K serially with
-// two groups of look-ahead and then costs 0.6 us per group whatever the token count (K = 4096:
-// 19.4 us from 17 to 256 tokens), the weight-streaming kernel for a few dozen tokens 11 us up to 32
-// tokens and 15-16 us up to 64.  So the streaming kernel takes 17..64 tokens, except where the tiled
-// kernel has the blocks to cover that latency: with the caller's scratch on layers with a long K
-// (K split over blocks; K = 14336, N = 4096: 22-23 us against 27 us at 32 tokens and 37 us at 64),
-// or with a grid of 64 x 128 tiles that fills the chip from 33 tokens on (K = 8192, N = 57344 at 64
-// tokens: 68 against 80 us; K = 4096, N = 28672: 23.7 against 24.5 us).
+// the layer rotating over 512 MB, as in a step of a model), on the Llama-shaped layers:
+//  * up to 32 tokens the weight-streaming kernel for a few dozen tokens (K = N = 4096: 11 against
+//    14.5 us for the tiled kernel), except on layers with a long K when the caller brings the
+//    scratch that lets the tiled kernel split K over blocks (K = 14336, N = 4096: 22 against 27 us);
+//  * from 33 tokens the tiled kernel with its small block shapes (K = N = 4096 at 64 tokens: 14.5
+//    against 15.4 us; K = 4096, N = 28672: 21 against 25 us; K = 8192, N = 57344: 67 against 81 us),
+//    except where its K loop is long, cannot be split for want of scratch, and the grid of 64 x 128
+//    tiles leaves CUs empty (K = 14336, N = 4096: 37 us for the streaming kernel, 50 us tiled).
 int auto_path(const mixllm_desc &d, const LinearParams &p)
 {
     if (d.M <= 16) return MIXLLM_PATH_DECODE;
@@ -168,7 +168,7 @@ int auto_path(const mixllm_desc &d, const LinearParams &p)
     const bool split = prefill_would_split(p);
     if (d.M <= 32) return (split && p.ng > 64) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
     const long tiles = (long)(p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
-    return (split || 4 * tiles >= 3L * cu_count()) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
+    return (p.ng < 64 || split || 4 * tiles >= 3L * cu_count()) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
 }
 
 // Which kernel a call takes: the caller's path argument with AUTO resolved, or a negative status

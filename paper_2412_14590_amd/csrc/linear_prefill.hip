@@ -47,6 +47,10 @@ constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each
 #ifndef MIXLLM_PREFILL_WD_LARGE
 #define MIXLLM_PREFILL_WD_LARGE 1   // 128 x 128 blocks
 #endif
+// groups an 8-bit tile requests its weights ahead of their use (1 or 3)
+#ifndef MIXLLM_PREFILL_L8
+#define MIXLLM_PREFILL_L8 3
+#endif
 // token tiles per band of the block order: 4, 8 and 16 measure within 2 % of each other
 #ifndef MIXLLM_PREFILL_BAND
 #define MIXLLM_PREFILL_BAND 4
@@ -85,6 +89,7 @@ struct Shape {
     static constexpr int RING = TM >= 2 ? 8 : 4;  // fragment registers (at least DFRAG + 2: the slot being overwritten is two MFMAs old)
     static constexpr int NB = TM >= 2 ? 2 : 1;    // token tiles whose MFMA chains alternate (a bundle)
     static constexpr int WD = WD_;                // groups between the request for packed 4-bit weights and the wait for them
+    static constexpr int L8 = MIXLLM_PREFILL_L8;  // groups between the request for 8-bit weights and their use
     static_assert(TM * 4 - DFRAG >= TM * 2 && DFRAG + 2 <= RING, "fragment requests must not pass the barrier or wrap the ring");
     static_assert(BM % (8 * NW) == 0, "A tile must split evenly over the waves");
     static_assert(TM % NB == 0 && (TM * 4) % RING == 0, "whole bundles of token tiles; slots wrap the fragment ring");
@@ -159,7 +164,16 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // (byte offsets of a lane inside the weight and metadata arrays fit 32 bits: checked on the host)
     const uint32_t b_voff = PART8 ? ((uint32_t)tile16 * (uint32_t)(p.K / 64) * 64 + (n32 & 15) + 16 * h) * 16
                                   : ((uint32_t)tile16 * (uint32_t)ng * 64 + (n32 & 15) + 16 * h) * 16;
-    v4i b[2][4];
+    // Operand sets.  Unpacked 4-bit groups alternate between two.  8-bit groups are loaded straight
+    // into them, L8 groups ahead, and then need L8 + 1 sets: with one group ahead a launch whose
+    // weights come from HBM spends 0.6 us per group waiting for them whatever the tile does
+    // (K = N = 4096 with 10 % 8-bit channels: 19.4 us from 17 to 256 tokens, 14 us without the
+    // 8-bit tiles); three groups ahead cover that latency.
+    // (The debug variant that adds the partials up as integers under per-group activation scales has
+    // no registers left for the ring and keeps one group of look-ahead.)
+    constexpr int L8 = (DUMP == 2 && !ACT_PT) ? 1 : C::L8, NBUF = PART8 ? L8 + 1 : 2;
+    static_assert(NBUF == 2 || NBUF == 4, "operand sets are indexed by the group number modulo 4");
+    v4i b[NBUF][4];
     // packed 4-bit weights are requested WD groups before the wait for them (hand-issued loads
     // only: with ordinary loads the wait below cannot count what is younger in the queue)
     // Raw (packed) weights of groups g + 1 .. g + 1 + WD are live at the middle of group g: WD + 1
@@ -170,7 +184,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     constexpr int NMETA = DUMP == 1 ? 1 : 2;   // load instructions load_meta issues for a 4-bit tile in the hand-issued variant
     v4i raw[NRAW][2];
     auto load_b = [&](int g, auto setc) {
-        constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW;
+        constexpr int set = decltype(setc)::value % NBUF, rset = decltype(setc)::value % NRAW;
         const int gc = min(g, g_hi - 1);
         if (PART8) {
             const uint8_t *base = (const uint8_t *)p.w8 + (size_t)gc * 2048;
@@ -229,7 +243,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // then unpack to zeros - together with a zero point of zero - where the linear multiplies the
     // group's partial by a zero scale)
     auto unpack_piece = [&](auto setc, auto dc, uint32_t zb, uint32_t keep) {
-        constexpr int set = decltype(setc)::value % 2, rset = decltype(setc)::value % NRAW, d = decltype(dc)::value;
+        constexpr int set = decltype(setc)::value % NBUF, rset = decltype(setc)::value % NRAW, d = decltype(dc)::value;
         constexpr int bj = d >> 1, e = d & 1;
         int lo, hi;
         uint32_t w = (uint32_t)raw[rset][bj & 1][(bj >> 1) * 2 + e];
@@ -295,6 +309,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     load_meta(g_lo / 4, meta_cur);
     load_b(g_lo, std::integral_constant<int, 0>{});
     if (!PART8) static_for<1, WD + 1>([&](auto gc) { load_b(g_lo + decltype(gc)::value, gc); });
+    else static_for<1, L8>([&](auto gc) { load_b(g_lo + decltype(gc)::value, gc); });
     load_a(g_lo, 0);
     load_a(g_lo + 1, 1);
     load_a(g_lo + 2, 2);
@@ -312,11 +327,31 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         load_reg_u16(sa_bits, sa_voff, p.xscale + min(g_lo + 1, g_hi - 1));
     }
     const float sw_row = (PART8 && DUMP != 1 && !PG8) ? (float)p.s8[rw] : 0.0f;
+    // Token scales of the epilogue (one per token), requested here where the registers allow it: the
+    // epilogue of a short launch otherwise pays a round trip to memory for them (about 1 us of the
+    // 14 us a layer of K = 4096 takes at 64 tokens).
+    constexpr bool EARLY_SA = ACT_PT && DUMP == 0 && TM <= 2;
+    uint32_t sa_early[EARLY_SA ? TM : 1][16];
+    if constexpr (EARLY_SA) {
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                load_reg_u16(sa_early[mt][r], (uint32_t)min(m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3), p.M - 1) * 2u, p.xscale);
+    }
     // everything above has landed (registers and LDS)
+    if constexpr (EARLY_SA) {
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) await_loads<0>(sa_early[mt][r]);
+    }
     await_loads<0>(meta_cur.s, meta_cur.z);
     await_loads<0>(sa_bits);
-    if (PART8) await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
-    else static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
+    if constexpr (PART8)
+        static_for<0, L8>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
+    else
+        static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
     __syncthreads();
     meta_nxt = meta_cur;
     if (!PART8) {
@@ -350,15 +385,17 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         if (DUMP == 1) asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
         uint32_t zb_next = 0;
         const uint32_t keep_next = g + 1 < g_hi ? 0xffffffffu : 0u;
-        // 8-bit weights need no unpack: group g+1 is requested here, straight into the operand
-        // registers group g-1 just vacated; this group's own request (one group old, only the
-        // previous middle's activation loads are younger) has to have landed
+        // 8-bit weights need no unpack: group g + L8 is requested here, straight into the operand
+        // registers group g-1 just vacated; this group's own request has to have landed.  It is L8
+        // groups old: issued after it were the activation loads of L8 middles and the weights of
+        // L8 - 1 groups (metadata and activation-scale requests of those middles are not counted:
+        // the wait then asks for a few loads more than it needs, all of them older than two groups).
         if (PART8) {
-            await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
-            load_b(g + 1, std::integral_constant<int, U + 1>{});
+            await_loads<L8 * LPW + 4 * (L8 - 1)>(b[U % NBUF][0], b[U % NBUF][1], b[U % NBUF][2], b[U % NBUF][3]);
+            load_b(g + L8, std::integral_constant<int, U + L8>{});
             if (DUMP == 2 && g >= g_hi) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) b[U % 2][j] = v4i{0, 0, 0, 0};
+                for (int j = 0; j < 4; ++j) b[U % NBUF][j] = v4i{0, 0, 0, 0};
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -384,11 +421,14 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 // activations; the scale request of the previous middle (group g+1's) is older than
                 // that middle's weights and activations, so with per-group activation scales the
                 // WD = 2 wait does not count a metadata request as young.  An 8-bit tile requests
-                // its weights at the start of a group: the 4 loads of group g+1 are the youngest.
+                // its weights at the start of a group: issued after group g+1's activations (two
+                // middles ago) were the weights of two groups and the previous middle's activations;
+                // with per-group activation scales the previous middle's scale request has to have
+                // landed as well, and with it the older of those two weight requests.
                 // (WD >= 2: the wait is bound by group g+1's activations, requested two middles ago,
                 // so the whole batch of the previous middle may stay in flight, however far ahead
                 // the weights run)
-                constexpr int YOUNGER = PART8 ? LPW + 4 : WD == 1 ? LPW : (U == 2 && ACT_PT ? NMETA : 0) + 2 + LPW;
+                constexpr int YOUNGER = PART8 ? ((!ACT_PT && DUMP != 1) || L8 == 1 ? LPW + 4 : LPW + 8) : WD == 1 ? LPW : (U == 2 && ACT_PT ? NMETA : 0) + 2 + LPW;
                 if (PART8) await_loads<YOUNGER>();
                 else await_loads<YOUNGER>(raw[(U + 1) % NRAW][0], raw[(U + 1) % NRAW][1]);
                 if constexpr (U == 3) await_loads<YOUNGER>(meta_nxt.s, meta_nxt.z);
@@ -414,7 +454,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
                 load_frag(std::integral_constant<int, U>{}, std::integral_constant<int, st + DFRAG>{});
             else
                 load_frag(std::integral_constant<int, (U + 1) % NSTAGE>{}, std::integral_constant<int, st + DFRAG - NSLOT>{});
-            P[s][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][j], j == 0 ? zero16 : P[s][i], 0, 0, 0);
+            P[s][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % NBUF][j], j == 0 ? zero16 : P[s][i], 0, 0, 0);
             finish4(P[s ^ 1][i], std::integral_constant<int, up>{}, std::integral_constant<int, j>{},
                     q == 0 ? sw_prev : sw_cur, gp, opaque0);
             if constexpr (!PART8 && st >= HALF) {
@@ -452,8 +492,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     // wait keeps them allocated until the data has arrived; without it they could be reused
     // (say for an epilogue address) and then be overwritten by a late load.
     static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
-    await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
-    await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
+    static_for<0, NBUF>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
     await_loads<0>(meta_nxt.s, meta_nxt.z);
     await_loads<0>(sa_bits);
     if (DUMP == 1) return;
@@ -495,7 +534,8 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            sa[r] = ACT_PT ? (float)p.xscale[min(m, p.M - 1)] : 1.0f;
+            if constexpr (EARLY_SA) sa[r] = half_bits_to_float(sa_early[mt][r]);
+            else sa[r] = ACT_PT ? (float)p.xscale[min(m, p.M - 1)] : 1.0f;
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -544,9 +584,12 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     for (int j = 0; j < 4; ++j) a_rd[j] = (mw0 + n32) * G + (((2 * j + h) ^ ((n32 >> 1) & 7)) << 4);
 
     const uint32_t b_voff = ((uint32_t)tile16 * (uint32_t)(p.K / 64) * 64 + (n32 & 15) + 16 * h) * 16;
-    v4i b[2][4];
+    // weights are requested L8 groups ahead into a ring of L8 + 1 operand sets (see prefill_block)
+    constexpr int L8 = C::L8, NBUF = L8 + 1;
+    static_assert(NBUF == 2 || NBUF == 4, "operand sets are indexed by the group number modulo 4");
+    v4i b[NBUF][4];
     auto load_b = [&](int g, auto setc) {
-        constexpr int set = decltype(setc)::value % 2;
+        constexpr int set = decltype(setc)::value % NBUF;
         const uint8_t *base = (const uint8_t *)p.w8 + (size_t)min(g, g_hi - 1) * 2048;
         load_reg16<0>(b[set][0], b_voff, base);
         load_reg16<512>(b[set][1], b_voff, base);
@@ -554,14 +597,29 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
         load_reg16<1536>(b[set][3], b_voff, base);
     };
 
-    load_b(g_lo, std::integral_constant<int, 0>{});
+    static_for<0, L8>([&](auto gc) { load_b(g_lo + decltype(gc)::value, gc); });
     load_a(g_lo, 0);
     load_a(g_lo + 1, 1);
     load_a(g_lo + 2, 2);
     static_assert(ACT_PT, "an integer sum over groups needs an activation scale that does not depend on the group");
     static_assert(DUMP != 1, "one accumulator over all of K: there is no per-group partial to dump");
     const float sw_row = (float)p.s8[rw];
-    await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
+    // token scales of the epilogue, requested up front where the registers allow it (see prefill_block)
+    constexpr bool EARLY_SA = DUMP == 0 && TM <= 2;
+    uint32_t sa_early[EARLY_SA ? TM : 1][16];
+    if constexpr (EARLY_SA) {
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                load_reg_u16(sa_early[mt][r], (uint32_t)min(m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3), p.M - 1) * 2u, p.xscale);
+            }
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) await_loads<0>(sa_early[mt][r]);
+    }
+    static_for<0, L8>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
     __syncthreads();
     v4i af[RING];
     // slot t: k step t / TM, token tile t % TM
@@ -579,21 +637,23 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
 
     auto group_step = [&](int g, auto uc) {
         constexpr int U = decltype(uc)::value;
-        // this group's weights were requested one group ago; only the previous middle's LPW
-        // activation loads are younger
-        await_loads<LPW>(b[U % 2][0], b[U % 2][1], b[U % 2][2], b[U % 2][3]);
-        load_b(g + 1, std::integral_constant<int, U + 1>{});
+        // this group's weights were requested L8 groups ago; issued after them were the activation
+        // loads of L8 middles and the weights of L8 - 1 groups
+        await_loads<L8 * LPW + 4 * (L8 - 1)>(b[U % NBUF][0], b[U % NBUF][1], b[U % NBUF][2], b[U % NBUF][3]);
+        load_b(g + L8, std::integral_constant<int, U + L8>{});
         if (g >= g_hi) {   // a group past the end (K/128 not a multiple of 4) must add nothing
 #pragma unroll
-            for (int j = 0; j < 4; ++j) b[U % 2][j] = v4i{0, 0, 0, 0};
+            for (int j = 0; j < 4; ++j) b[U % NBUF][j] = v4i{0, 0, 0, 0};
         }
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, NSLOT>([&](auto stc) {
             constexpr int st = decltype(stc)::value;
             if constexpr (st == HALF) {
-                // group g+1's activations were requested two middles ago; younger than them are
-                // the weights of group g+1 (4 loads) and the activations of group g+2 (LPW loads)
-                await_loads<LPW + 4>();
+                // group g+1's activations were requested two middles ago; issued after them were
+                // the weights of two groups (4 loads each; with one group of look-ahead the older
+                // of the two has been waited for at the start of this group) and the activations
+                // of group g+2 (LPW loads)
+                await_loads<(L8 == 1 ? LPW + 4 : LPW + 8)>();
                 mid_group_barrier<false>();
                 load_a(g + 3, (U + 3) % NSTAGE);
                 __builtin_amdgcn_sched_barrier(0);
@@ -602,7 +662,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
                 load_frag(std::integral_constant<int, U>{}, std::integral_constant<int, st + DFRAG>{});
             else
                 load_frag(std::integral_constant<int, (U + 1) % NSTAGE>{}, std::integral_constant<int, st + DFRAG - NSLOT>{});
-            P[st % TM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % 2][st / TM], P[st % TM], 0, 0, 0);
+            P[st % TM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[st % RING], b[U % NBUF][st / TM], P[st % TM], 0, 0, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -615,8 +675,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
         group_step(g + 3, std::integral_constant<int, 3>{});
     }
     // drain (see prefill_block): nothing in flight towards this block's LDS or registers
-    await_loads<0>(b[0][0], b[0][1], b[0][2], b[0][3]);
-    await_loads<0>(b[1][0], b[1][1], b[1][2], b[1][3]);
+    static_for<0, NBUF>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
 
     if (DUMP == 0 && p.kparts > 1) {   // K split over several blocks: see prefill_block
         const bool valid = t16 < p.ntiles8;
@@ -635,7 +694,8 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            sa[r] = (float)p.xscale[min(m, p.M - 1)];
+            if constexpr (EARLY_SA) sa[r] = half_bits_to_float(sa_early[mt][r]);
+            else sa[r] = (float)p.xscale[min(m, p.M - 1)];
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -690,14 +750,22 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
 // K split over several blocks: the parts' fp32 sums (workspace, [part][token][padded concatenated
 // row]) are added in part order - a fixed order, no atomics - scaled by the token's activation
 // scale where that is one per token, converted and scattered (Sec. 3.4).
+constexpr int MAX_KPARTS = 8;   // K parts a launch is split into at most
 __global__ __launch_bounds__(256) void prefill_reduce_kernel(LinearParams p)
 {
     // four consecutive rows of the padded concatenation per thread (p.np is a multiple of 16)
     const int jp0 = (blockIdx.x * 256 + threadIdx.x) * 4, m = blockIdx.y;
     if (jp0 >= p.np) return;
     const int n8p = p.ntiles8 * TILE_N;
+    // all parts are requested before the first is added (one round trip instead of one per part)
+    v4f part[MAX_KPARTS];
+#pragma unroll
+    for (int kp = 0; kp < MAX_KPARTS; ++kp)   // (past the last part: a re-read of the last one, not added)
+        part[kp] = *(const v4f *)(p.partials + ((size_t)min(kp, p.kparts - 1) * p.M + m) * p.np + jp0);
     v4f v = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int kp = 0; kp < p.kparts; ++kp) v += *(const v4f *)(p.partials + ((size_t)kp * p.M + m) * p.np + jp0);
+#pragma unroll
+    for (int kp = 0; kp < MAX_KPARTS; ++kp)
+        if (kp < p.kparts) v += part[kp];
     const float sa = p.act_per_token ? (float)p.xscale[m] : 1.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -837,15 +905,18 @@ static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &q
 {
     const int quads = (p.ng + 3) / 4;
     qpp = quads;
-    if (p.P || p.S || p.ng < 64) return 1;
+#ifdef MIXLLM_KSPLIT_ENV
+    const char *forced = getenv("MIXLLM_KPARTS");   // measurement builds only: the number of parts from the environment
+#else
+    const char *forced = nullptr;
+#endif
+    if (p.P || p.S || (p.ng < 64 && !forced)) return 1;
     const PrefillGrid g = grid_of(p, 32 * tm, tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128);
     const long blocks = (long)g.nbm * (g.nb8 + g.nb4), slots = 2L * cu_count();
     const size_t part_bytes = (size_t)p.M * p.np * sizeof(float);
-    long kp = std::min<long>(8, std::min<long>((slots + blocks / 2) / blocks, quads / 2));
+    long kp = std::min<long>(MAX_KPARTS, std::min<long>((slots + blocks / 2) / blocks, quads / 2));
     kp = std::min<long>(kp, (long)(std::min<size_t>(cap_bytes, (size_t)12 << 20) / part_bytes));
-#ifdef MIXLLM_KSPLIT_ENV
-    if (const char *e = getenv("MIXLLM_KPARTS")) kp = std::min<long>(atol(e), std::min<long>(quads, (long)(cap_bytes / part_bytes)));
-#endif
+    if (forced) kp = std::min<long>(std::min<long>(atol(forced), MAX_KPARTS), std::min<long>(quads, (long)(cap_bytes / part_bytes)));
     if (kp <= 1) return 1;
     qpp = (int)((quads + kp - 1) / kp);
     return (quads + qpp - 1) / qpp;   // parts of qpp groups of 4: never more than kp
