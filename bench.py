@@ -596,7 +596,8 @@ def main():
     if not args.no_extras:
         from paper_2412_14590_amd import probe
         result["measured_ceilings"] = {"hbm_read_GBps_4GiB": probe.hbm_read_gbs(),
-                                       "mfma_int8_TOPS_register_resident": probe.mfma_int8_tops(4)}
+                                       "mfma_int8_TOPS_register_resident": probe.mfma_int8_tops(4),
+                                       "us_per_launch_of_a_near_empty_kernel_in_a_graph": probe.kernel_floor_us()}
         log(f"[bench] measured ceilings: {result['measured_ceilings']}")
     if args.copy_probe:
         from paper_2412_14590_amd import probe

@@ -124,7 +124,11 @@ def build(force: bool = True, verbose: bool = False) -> str:
     for src, pr in procs:
         out, _ = pr.communicate()
         if src in NO_SPILL and pr.returncode == 0:
-            _check_no_scratch(src, out)
+            try:
+                _check_no_scratch(src, out)
+            except RuntimeError:
+                os.remove(os.path.join(objdir, src.replace(".hip", ".o")))   # a later build must not take it for up to date
+                raise
             out = "\n".join(l for l in out.splitlines() if "kernel-resource-usage" not in l and not l.lstrip().startswith(("|", "^")) and not re.match(r"\s*\d+ \|", l))
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if pr.returncode != 0:
@@ -146,7 +150,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
         out, _ = pr.communicate()
         if pr.returncode != 0:
             raise RuntimeError(f"hipcc -S failed for {src}:\n{out}")
-        check_hand_issued_loads(open(a).read(), src)
+        try:
+            check_hand_issued_loads(open(a).read(), src)
+        except RuntimeError:
+            for stale in (a, os.path.join(objdir, src.replace(".hip", ".o"))):   # a later build must check again
+                if os.path.exists(stale):
+                    os.remove(stale)
+            raise
     subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     if variant:
         return LIB

@@ -63,6 +63,23 @@ constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each
 #define MIXLLM_PREFILL_WN_LARGE 4
 #endif
 
+// Measurement builds only (-DMIXLLM_STAMPS): thread 0 of every block records the constant 100 MHz
+// clock at a few points of its life into a caller-supplied array [blocks][8].
+#ifdef MIXLLM_STAMPS
+__device__ unsigned long long *g_stamps;
+#define MIXLLM_STAMP(i)                                                                          \
+    do {                                                                                         \
+        if constexpr (DUMP == 0) {   /* the linear only; used where a template parameter DUMP is in scope */ \
+            unsigned long long t_;                                                               \
+            asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t_)::"memory");       \
+            unsigned long long *sp_ = g_stamps;                                                  \
+            if (sp_ && threadIdx.x == 0) sp_[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8 + (i)] = t_; \
+        }                                                                                        \
+    } while (0)
+#else
+#define MIXLLM_STAMP(i)
+#endif
+
 // compile-time loop: f(std::integral_constant<int, I>) for I in [I, N)
 template <int I, int N, typename F>
 static __device__ inline void static_for(F &&f)
@@ -327,25 +344,30 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         load_reg_u16(sa_bits, sa_voff, p.xscale + min(g_lo + 1, g_hi - 1));
     }
     const float sw_row = (PART8 && DUMP != 1 && !PG8) ? (float)p.s8[rw] : 0.0f;
-    // Token scales of the epilogue (one per token), requested here where the registers allow it: the
-    // epilogue of a short launch otherwise pays a round trip to memory for them (about 1 us of the
-    // 14 us a layer of K = 4096 takes at 64 tokens).
-    constexpr bool EARLY_SA = ACT_PT && DUMP == 0 && TM <= 2;
-    uint32_t sa_early[EARLY_SA ? TM : 1][16];
-    if constexpr (EARLY_SA) {
+    // Token scales of the epilogue (one per token): all 16 TM of a lane are requested together, by
+    // hand, ahead of the epilogue - in the prologue where the registers allow it (the epilogue of a
+    // short launch otherwise pays a round trip to memory for them), else after the K loop and its
+    // drain: one round trip for all of them.  (Written as plain loads inside the
+    // epilogue they cost one round trip per token tile: the compiler does not move the next
+    // tile's loads above the stores of the previous one.)
+    constexpr bool HAND_SA = ACT_PT && DUMP == 0, EARLY_SA = HAND_SA && TM <= 2;
+    uint32_t sa_ep[HAND_SA ? TM : 1][16];
+    auto request_token_scales = [&]() {
 #pragma unroll
         for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                load_reg_u16(sa_early[mt][r], (uint32_t)min(m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3), p.M - 1) * 2u, p.xscale);
-    }
-    // everything above has landed (registers and LDS)
-    if constexpr (EARLY_SA) {
+                load_reg_u16(sa_ep[mt][r], (uint32_t)min(m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3), p.M - 1) * 2u, p.xscale);
+    };
+    auto await_token_scales = [&]() {
 #pragma unroll
         for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) await_loads<0>(sa_early[mt][r]);
-    }
+            for (int r = 0; r < 16; ++r) await_loads<0>(sa_ep[mt][r]);
+    };
+    if constexpr (EARLY_SA) request_token_scales();
+    // everything above has landed (registers and LDS)
+    if constexpr (EARLY_SA) await_token_scales();
     await_loads<0>(meta_cur.s, meta_cur.z);
     await_loads<0>(sa_bits);
     if constexpr (PART8)
@@ -353,6 +375,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     else
         static_for<0, NRAW>([&](auto rc) { await_loads<0>(raw[decltype(rc)::value][0], raw[decltype(rc)::value][1]); });
     __syncthreads();
+    MIXLLM_STAMP(1);
     meta_nxt = meta_cur;
     if (!PART8) {
         const uint32_t zb = zbias(meta_cur.z & 15);
@@ -480,6 +503,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
         group_step(g + 3, std::integral_constant<int, 3>{});
         meta_cur = meta_nxt;
     }
+    MIXLLM_STAMP(2);
     const int g_last = g_lo + ((g_hi - g_lo + 3) & ~3) - 1;   // group index the pending pair belongs to (may be a phantom one)
     // the last bundle of the last group is still waiting for its rescale
     static_for<0, SB>([&](auto tc) {
@@ -495,6 +519,11 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
     static_for<0, NBUF>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
     await_loads<0>(meta_nxt.s, meta_nxt.z);
     await_loads<0>(sa_bits);
+    if constexpr (HAND_SA && !EARLY_SA) {   // (operand and int32 accumulator registers are free now)
+        request_token_scales();
+        await_token_scales();
+    }
+    MIXLLM_STAMP(3);
     if (DUMP == 1) return;
     if (DUMP == 2) {
         // (the channel passes through an empty asm statement so that no store address is computed,
@@ -534,7 +563,7 @@ static __device__ inline void prefill_block(const LinearParams &p, int m0, int t
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            if constexpr (EARLY_SA) sa[r] = half_bits_to_float(sa_early[mt][r]);
+            if constexpr (HAND_SA) sa[r] = half_bits_to_float(sa_ep[mt][r]);
             else sa[r] = ACT_PT ? (float)p.xscale[min(m, p.M - 1)] : 1.0f;
         }
 #pragma unroll
@@ -604,20 +633,25 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     static_assert(ACT_PT, "an integer sum over groups needs an activation scale that does not depend on the group");
     static_assert(DUMP != 1, "one accumulator over all of K: there is no per-group partial to dump");
     const float sw_row = (float)p.s8[rw];
-    // token scales of the epilogue, requested up front where the registers allow it (see prefill_block)
-    constexpr bool EARLY_SA = DUMP == 0 && TM <= 2;
-    uint32_t sa_early[EARLY_SA ? TM : 1][16];
+    // token scales of the epilogue, requested by hand ahead of it (see prefill_block)
+    constexpr bool HAND_SA = DUMP == 0, EARLY_SA = HAND_SA && TM <= 2;
+    uint32_t sa_ep[HAND_SA ? TM : 1][16];
+    auto request_token_scales = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                load_reg_u16(sa_ep[mt][r], (uint32_t)min(m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3), p.M - 1) * 2u, p.xscale);
+    };
+    auto await_token_scales = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) await_loads<0>(sa_ep[mt][r]);
+    };
     if constexpr (EARLY_SA) {
-#pragma unroll
-        for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                load_reg_u16(sa_early[mt][r], (uint32_t)min(m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3), p.M - 1) * 2u, p.xscale);
-            }
-#pragma unroll
-        for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) await_loads<0>(sa_early[mt][r]);
+        request_token_scales();
+        await_token_scales();
     }
     static_for<0, L8>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
     __syncthreads();
@@ -676,6 +710,10 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
     }
     // drain (see prefill_block): nothing in flight towards this block's LDS or registers
     static_for<0, NBUF>([&](auto sc) { await_loads<0>(b[decltype(sc)::value][0], b[decltype(sc)::value][1], b[decltype(sc)::value][2], b[decltype(sc)::value][3]); });
+    if constexpr (HAND_SA && !EARLY_SA) {   // (the operand registers are free now)
+        request_token_scales();
+        await_token_scales();
+    }
 
     if (DUMP == 0 && p.kparts > 1) {   // K split over several blocks: see prefill_block
         const bool valid = t16 < p.ntiles8;
@@ -694,7 +732,7 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mw0 + mt * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-            if constexpr (EARLY_SA) sa[r] = half_bits_to_float(sa_early[mt][r]);
+            if constexpr (HAND_SA) sa[r] = half_bits_to_float(sa_ep[mt][r]);
             else sa[r] = (float)p.xscale[min(m, p.M - 1)];
         }
 #pragma unroll
@@ -712,6 +750,7 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
                                                                          int nb4, int per4, int per8, int band)
 {
     // K split over p.kparts blocks (blockIdx.y): part kp takes 4 * p.quads_per_part groups
+    MIXLLM_STAMP(0);
     const int kp = blockIdx.y;
     const int g_lo = kp * p.quads_per_part * 4, g_hi = min(p.ng, g_lo + p.quads_per_part * 4);
     // dynamic LDS (more than the 64 KB a static array may take): the activation stages, then
@@ -745,6 +784,11 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
             prefill_block<C, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
     } else
         prefill_block<C, DUMP, ACT_PT, false, false, ASYNC>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
+#ifdef MIXLLM_STAMPS
+    MIXLLM_STAMP(4);                                   // stores issued
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // ... and acknowledged
+    MIXLLM_STAMP(5);
+#endif
 }
 
 // K split over several blocks: the parts' fp32 sums (workspace, [part][token][padded concatenated
@@ -781,6 +825,13 @@ __global__ __launch_bounds__(256) void prefill_reduce_kernel(LinearParams p)
         p.y[(size_t)m * p.N + p.perm[j]] = (half_t)(v[i] * sa);
     }
 }
+
+#ifdef MIXLLM_STAMPS
+extern "C" int mixllm_debug_set_stamps(void *stamps)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_stamps), &stamps, sizeof stamps);
+}
+#endif
 
 // The kernels take more dynamic LDS than the default limit; raising the limit is a per-function
 // attribute, set on the first launch of each instantiation (per device: the attribute belongs to

@@ -54,3 +54,24 @@ def hbm_read_gbs(nbytes=4 << 30, blocks=256 * 16) -> float:
 def copy(src: torch.Tensor, dst: torch.Tensor, blocks=256 * 16):
     lib().mixllm_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), blocks,
                             torch.cuda.current_stream().cuda_stream)
+
+
+def kernel_floor_us(reps=200, blocks=256, nbytes=1 << 20) -> float:
+    """Time per launch of a kernel that does next to nothing (every block reads 4 KB and writes
+    nothing), launched `reps` times back to back on one stream and replayed from a HIP graph:
+    the share of a short kernel's duration that no kernel design removes (dispatch, the cache
+    write-back and invalidate between dependent launches)."""
+    src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(4, dtype=torch.int32, device="cuda")
+    launch = lambda st: lib().mixllm_probe_read(src.data_ptr(), nbytes, blocks, out.data_ptr(), st)
+    launch(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(reps):
+                launch(side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    return _time(g.replay) / reps * 1e6
