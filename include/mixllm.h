@@ -298,9 +298,11 @@ int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream);
  * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS;
  * path = MIXLLM_PATH_MID: plan[0..4] = blocks of the 8-bit part, of the 4-bit part, quarter tiles
  * per virtual tile of the 8-bit and of the 4-bit part, bytes of LDS; path = MIXLLM_PATH_PREFILL:
- * plan[0..9] = token rows and channels of a block tile, token tiles, channel tiles of the 8-bit and
- * of the 4-bit part, blocks launched per K part, token tiles per band of the block order, bytes of LDS,
- * K parts (with linear_workspace_bytes of scratch), quantization groups per K part.  plan must hold
+ * plan[0..12] = token rows and channels of a block tile of the 4-bit part, its token tiles, channel
+ * tiles of the 8-bit and of the 4-bit part, blocks launched per K part, token tiles per band of the
+ * block order (4-bit part), bytes of LDS, K parts (with linear_workspace_bytes of scratch),
+ * quantization groups per K part, then token rows of a block tile of the 8-bit part (the 4-bit
+ * part's, or half of that in a short launch of 128-row tiles), its token tiles and its token tiles per band.  plan must hold
  * 16 ints.  Returns EUNSUPPORTED when the path does not cover the shape, EINVAL for other
  * paths.
  */

@@ -167,7 +167,7 @@ bool prefill_covers(const LinearParams &p);
 size_t prefill_scratch_bytes(const LinearParams &p);
 // true when the tiled kernel, given p.partials / p.partials_cap, would split K for `p`
 bool prefill_would_split(const LinearParams &p);
-bool prefill_plan(const LinearParams &p, int out[10]);
+bool prefill_plan(const LinearParams &p, int out[13]);
 // path for 17..128 tokens (linear_mid.hip)
 bool mid_covers(const LinearParams &p);
 int launch_linear_mid(const LinearParams &p, hipStream_t st);

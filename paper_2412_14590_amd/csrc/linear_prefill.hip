@@ -51,6 +51,14 @@ constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each
 #ifndef MIXLLM_PREFILL_L8
 #define MIXLLM_PREFILL_L8 3
 #endif
+// 1: in a launch of 128 x 128 blocks that is at most two rounds of blocks long, the 8-bit part runs in
+// blocks of 64 x 128 (0: never).  Measured at 2048 tokens, same machine, equal against half-height
+// 8-bit tiles: K = N = 4096 56.2 -> 51.5 us, K = 14336, N = 4096 164.5 -> 157.6, K = 4096, N = 6144
+// 75.4 -> 76.0; the layer of N = 28672 (seven rounds) 313 -> 324 us, which is why long launches keep
+// the full tiles; blocks of 32 x 128 for the 8-bit part of a 64 x 128 launch measured 4-7 % slower.
+#ifndef MIXLLM_PREFILL_HALF8
+#define MIXLLM_PREFILL_HALF8 1
+#endif
 // token tiles per band of the block order: 4, 8 and 16 measure within 2 % of each other
 #ifndef MIXLLM_PREFILL_BAND
 #define MIXLLM_PREFILL_BAND 4
@@ -105,6 +113,8 @@ struct Shape {
     static constexpr int DFRAG = TM >= 4 ? 6 : 2 * TM;
     static constexpr int RING = TM >= 2 ? 8 : 4;  // fragment registers (at least DFRAG + 2: the slot being overwritten is two MFMAs old)
     static constexpr int NB = TM >= 2 ? 2 : 1;    // token tiles whose MFMA chains alternate (a bundle)
+    // the shape the 8-bit part of a short launch runs in: half the token rows (see linear_prefill_kernel)
+    using Half = Shape<WM_, WN_, (TM_ == 4 && MIXLLM_PREFILL_HALF8 ? 2 : TM_), WD_>;
     static constexpr int WD = WD_;                // groups between the request for packed 4-bit weights and the wait for them
     static constexpr int L8 = MIXLLM_PREFILL_L8;  // groups between the request for 8-bit weights and their use
     static_assert(TM * 4 - DFRAG >= TM * 2 && DFRAG + 2 <= RING, "fragment requests must not pass the barrier or wrap the ring");
@@ -746,8 +756,8 @@ static __device__ inline void prefill_block_w8_channel_scale(const LinearParams 
 }
 
 template <typename C, int MINW, int DUMP, bool ACT_PT, bool W8PC>
-__global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm, int nb8,
-                                                                         int nb4, int per4, int per8, int band)
+__global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(LinearParams p, int nbm4, int nbm8, int nb8,
+                                                                         int nb4, int per4, int per8, int band4, int band8, int half8)
 {
     // K split over p.kparts blocks (blockIdx.y): part kp takes 4 * p.quads_per_part groups
     MIXLLM_STAMP(0);
@@ -766,9 +776,17 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
     // ids followed by a contiguous range of the 8-bit ids, so that every XCD ends on the cheap
     // tiles: 4-bit tiles take about twice as long as 8-bit ones (unpack, per-group rescale), and
     // the cheap ones fill the last, partly empty round of the grid.
+    // Where the host says so (half8: a launch of 128 x 128 blocks at most two rounds long) the 8-bit
+    // tiles are half as tall as the 4-bit ones (C::Half).  Blocks are dispatched in the order of
+    // their ids, so the 8-bit blocks - the last of every XCD - are what runs while the last 4-bit
+    // blocks finish, and the finer they are the less of the chip idles then: with N = 4096 and 10 %
+    // 8-bit channels a launch has 33 column tiles, 2048 tokens make 528 blocks of 128 x 128 for 512
+    // places, and the 16 late ones cost 15 % of the launch (58 us against 50 us for 32 column
+    // tiles); as 128 blocks of 64 x 128 they fit the shadow of the 4-bit blocks.
+    using C8 = typename C::Half;
     const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
     const bool part8 = i >= per4;
-    const int nb = part8 ? nb8 : nb4;
+    const int nb = part8 ? nb8 : nb4, nbm = part8 ? nbm8 : nbm4, band = part8 ? band8 : band4;
     const int L = part8 ? xcd * per8 + (i - per4) : xcd * per4 + i;
     if (L >= nbm * nb) return;
     const int bd = L / (band * nb);              // bands before the last one are full
@@ -777,11 +795,21 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
     const int bn = r / w, bm = bd * band + r % w;
     constexpr int T16 = C::BN / TILE_N;
     constexpr bool ASYNC = true;   // every variant issues its loads by hand; spill free (checked by the build)
-    if (part8) {
+    auto tile8 = [&](auto shape) {
+        using S = decltype(shape);
         if constexpr (W8PC && ACT_PT && DUMP != 1)
-            prefill_block_w8_channel_scale<C, ACT_PT, DUMP>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
+            prefill_block_w8_channel_scale<S, ACT_PT, DUMP>(p, bm * S::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
         else
-            prefill_block<C, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
+            prefill_block<S, DUMP, ACT_PT, true, !W8PC, ASYNC>(p, bm * S::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
+    };
+    if (part8) {
+        // (8-bit tiles of 128 rows with a weight scale per group are not built: they do not fit the
+        // register file next to the ring of operand sets; that granularity always takes the half tiles)
+        if constexpr (!std::is_same<C8, C>::value && W8PC) {
+            if (half8) tile8(C8{});
+            else tile8(C{});
+        } else
+            tile8(C8{});
     } else
         prefill_block<C, DUMP, ACT_PT, false, false, ASYNC>(p, bm * C::BM, bn * T16, g_lo, g_hi, kp, lds_a, lds_sa);
 #ifdef MIXLLM_STAMPS
@@ -837,8 +865,8 @@ extern "C" int mixllm_debug_set_stamps(void *stamps)
 // attribute, set on the first launch of each instantiation (per device: the attribute belongs to
 // the loaded code object of the current device).
 template <typename C, typename K>
-static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStream_t st, const LinearParams &p, int nbm,
-                          int nb8, int nb4, int per4, int per8, int band)
+static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStream_t st, const LinearParams &p, int nbm4,
+                          int nbm8, int nb8, int nb4, int per4, int per8, int band4, int band8, int half8)
 {
     const size_t lds_bytes = (size_t)NSTAGE * C::A_STAGE + (with_sa ? (size_t)NSTAGE * C::BM * sizeof(float) : 16);
     // (kernel, device) pairs already configured; a handful of instantiations exist
@@ -861,26 +889,32 @@ static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStre
             if (ndone < 64) done[ndone++] = Done{(const void *)kernel, dev};
         }
     }
-    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm, nb8, nb4, per4, per8, band);
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, nbm4, nbm8, nb8, nb4, per4, per8, band4, band8, half8);
     if (p.kparts > 1)
         hipLaunchKernelGGL(prefill_reduce_kernel, dim3((p.np / 4 + 255) / 256, p.M), dim3(256), 0, st, p);
     return (int)hipGetLastError();
 }
 
-// the grid of a launch: token tiles, channel tiles of either part, logical block ids per XCD of
-// either part, token tiles per band (see linear_prefill_kernel)
+// the grid of a launch: token tiles of either part (BM rows for the 4-bit part; for the 8-bit part
+// half of that where a launch of 128 x 128 blocks is at most two rounds of blocks long), channel
+// tiles of either part, logical block ids per XCD of either part, token tiles per band of either part
+// (see linear_prefill_kernel)
 struct PrefillGrid {
-    int nbm, nb8, nb4, per4, per8, band;
+    int bm8, nbm4, nbm8, nb8, nb4, per4, per8, band4, band8;
 };
 static PrefillGrid grid_of(const LinearParams &p, int BM, int BN)
 {
     PrefillGrid g;
-    g.nbm = (p.M + BM - 1) / BM;
+    g.nbm4 = (p.M + BM - 1) / BM;
     g.nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN;
     g.nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
-    g.per4 = (g.nbm * g.nb4 + 7) / 8;
-    g.per8 = (g.nbm * g.nb8 + 7) / 8;
-    g.band = min(MIXLLM_PREFILL_BAND, g.nbm);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
+    const bool half8 = MIXLLM_PREFILL_HALF8 && BM == 128 && ((long)g.nbm4 * (g.nb4 + g.nb8) <= 4L * cu_count() || !p.w8_per_channel || p.P);
+    g.bm8 = half8 ? BM / 2 : BM;
+    g.nbm8 = (p.M + g.bm8 - 1) / g.bm8;
+    g.per4 = (g.nbm4 * g.nb4 + 7) / 8;
+    g.per8 = (g.nbm8 * g.nb8 + 7) / 8;
+    g.band4 = min(MIXLLM_PREFILL_BAND, g.nbm4);   // 4 measured best on the Llama shapes (8 and 2 within 2 %, whole columns 5 % slower)
+    g.band8 = min(MIXLLM_PREFILL_BAND * (BM / g.bm8), g.nbm8);   // the same token rows per band
     return g;
 }
 
@@ -888,10 +922,11 @@ template <typename C, int MINW>
 static int launch_shape(const LinearParams &p, hipStream_t st)
 {
     const PrefillGrid gr = grid_of(p, C::BM, C::BN);
-    const int nbm = gr.nbm, nb8 = gr.nb8, nb4 = gr.nb4, per4 = gr.per4, per8 = gr.per8, band = gr.band;
-    dim3 grid((per4 + per8) * 8, p.kparts), block(C::THREADS);
+    static_assert(C::Half::THREADS == C::THREADS && C::Half::BN == C::BN, "both parts run in blocks of the same width");
+    dim3 grid((gr.per4 + gr.per8) * 8, p.kparts), block(C::THREADS);
     auto go = [&](auto kernel, bool with_sa) {
-        return launch_variant<C>(kernel, with_sa, grid, block, st, p, nbm, nb8, nb4, per4, per8, band);
+        return launch_variant<C>(kernel, with_sa, grid, block, st, p, gr.nbm4, gr.nbm8, gr.nb8, gr.nb4, gr.per4, gr.per8, gr.band4, gr.band8,
+                                 gr.bm8 != C::BM);
     };
     // per-group partials (debug entry point): every tile through the per-group pipeline
     if (p.P) return go(linear_prefill_kernel<C, MINW, 1, true, false>, false);
@@ -963,7 +998,7 @@ static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &q
 #endif
     if (p.P || p.S || (p.ng < 64 && !forced)) return 1;
     const PrefillGrid g = grid_of(p, 32 * tm, tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128);
-    const long blocks = (long)g.nbm * (g.nb8 + g.nb4), slots = 2L * cu_count();
+    const long blocks = (long)g.nbm4 * g.nb4 + (long)g.nbm8 * g.nb8, slots = 2L * cu_count();
     const size_t part_bytes = (size_t)p.M * p.np * sizeof(float);
     long kp = std::min<long>(MAX_KPARTS, std::min<long>((slots + blocks / 2) / blocks, quads / 2));
     kp = std::min<long>(kp, (long)(std::min<size_t>(cap_bytes, (size_t)12 << 20) / part_bytes));
@@ -1012,10 +1047,11 @@ int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
     }
 }
 
-// the launch plan as ten integers (token rows and channels of a block tile, token tiles, channel
-// tiles of the 8-bit and of the 4-bit part, blocks launched per K part, token tiles per band, bytes of
-// LDS, K parts, groups per K part), for the host-side test of the block -> tile mapping
-bool prefill_plan(const LinearParams &p, int out[10])
+// the launch plan as thirteen integers (token rows and channels of a block tile of the 4-bit part, its
+// token tiles, channel tiles of the 8-bit and of the 4-bit part, blocks launched per K part, token tiles
+// per band of the 4-bit part, bytes of LDS, K parts, groups per K part, then token rows, token tiles and
+// token tiles per band of the 8-bit part), for the host-side test of the block -> tile mapping
+bool prefill_plan(const LinearParams &p, int out[13])
 {
     if (!prefill_covers(p)) return false;
     const int tm = token_tiles_per_wave(p);
@@ -1023,15 +1059,18 @@ bool prefill_plan(const LinearParams &p, int out[10])
     const PrefillGrid g = grid_of(p, BM, BN);
     out[0] = BM;
     out[1] = BN;
-    out[2] = g.nbm;
+    out[2] = g.nbm4;
     out[3] = g.nb8;
     out[4] = g.nb4;
     out[5] = (g.per4 + g.per8) * 8;
-    out[6] = g.band;
+    out[6] = g.band4;
     out[7] = NSTAGE * BM * G + ((!p.act_per_token && !p.P) ? NSTAGE * BM * (int)sizeof(float) : 16);   // (p.P is never set here)
     int qpp;
     out[8] = choose_kparts(p, tm, ~(size_t)0, qpp);   // blocks sharing a K range when the caller brings the scratch for it
     out[9] = 4 * qpp;                                 // quantization groups per part
+    out[10] = g.bm8;                                  // token rows, token tiles and token tiles per band of the 8-bit part
+    out[11] = g.nbm8;
+    out[12] = g.band8;
     return true;
 }
 

@@ -132,7 +132,7 @@ def check_prefill_grid(M, K, N, n8, act_group=None):
     d = binding._desc(M, K, N, n8, act_group, None)
     rc = mx.lib().mixllm_debug_work_split(C.byref(d), mx.PATH_PREFILL, C.cast(out, C.c_void_p))
     assert rc == 0
-    BM, BN, nbm, nb8, nb4, blocks, band, lds, kparts, groups_per_part = list(out)[:10]
+    BM, BN, nbm, nb8, nb4, blocks, band, lds, kparts, groups_per_part, BM8, nbm8, band8 = list(out)[:13]
     t8, t4 = tiles(N, n8)
     # K split over blocks (when the caller brings the scratch): whole groups of 4 quantization groups per
     # part, the parts cover K exactly, no part is empty; only layers with a long K are split, into at
@@ -141,36 +141,40 @@ def check_prefill_grid(M, K, N, n8, act_group=None):
     assert 1 <= kparts <= 8 and groups_per_part % 4 == 0
     assert (kparts - 1) * groups_per_part < ng <= kparts * groups_per_part
     if kparts > 1:
-        ntile = nbm * (nb8 + nb4)
+        ntile = nbm * nb4 + nbm8 * nb8
         assert ng >= 64 and groups_per_part >= 8 and ntile * kparts <= 2 * 256 + ntile // 2
         assert kparts * M * (t8 + t4) * 16 * 4 <= 12 << 20
     assert BM <= 32 or M > 32
     assert BM in (32, 64, 128) and BN == 128
     assert nbm == -(-M // BM) and nb8 == -(-t8 * 16 // BN) and nb4 == -(-t4 * 16 // BN)
+    # in a launch of 128 x 128 blocks at most two rounds of blocks long (two blocks per CU at a time) the
+    # 8-bit part runs in tiles half as tall, banded over the same token rows
+    assert BM8 == (64 if BM == 128 and nbm * (nb8 + nb4) <= 4 * 256 else BM)
+    assert nbm8 == -(-M // BM8) and 1 <= band8 <= min(4 * BM // BM8, nbm8)
     assert 1 <= band <= min(4, nbm) and lds <= 80 * 1024 and blocks % 8 == 0
     # the shape rule: the largest block tile whose grid still has about one block per CU or more
     nbn = nb8 + nb4
     if act_group == 128:
         assert BM <= 64
-    per4, per8 = -(-nbm * nb4 // 8), -(-nbm * nb8 // 8)
+    per4, per8 = -(-nbm * nb4 // 8), -(-nbm8 * nb8 // 8)
     assert blocks == 8 * (per4 + per8)
     seen = set()
     for b in range(blocks):
         xcd, i = b & 7, b >> 3
         part8 = i >= per4
-        nb = nb8 if part8 else nb4
+        nb, nbm_p, band_p = (nb8, nbm8, band8) if part8 else (nb4, nbm, band)
         L = xcd * per8 + (i - per4) if part8 else xcd * per4 + i
-        if L >= nbm * nb:
+        if L >= nbm_p * nb:
             continue
-        bd = L // (band * nb)
-        w = min(band, nbm - bd * band)
-        r = L - bd * band * nb
-        bn, bm = r // w, bd * band + r % w
-        assert 0 <= bm < nbm and 0 <= bn < nb, (b, bm, bn)
+        bd = L // (band_p * nb)
+        w = min(band_p, nbm_p - bd * band_p)
+        r = L - bd * band_p * nb
+        bn, bm = r // w, bd * band_p + r % w
+        assert 0 <= bm < nbm_p and 0 <= bn < nb, (b, bm, bn)
         key = (part8, bm, bn)
         assert key not in seen
         seen.add(key)
-    assert len(seen) == nbm * (nb8 + nb4)
+    assert len(seen) == nbm * nb4 + nbm8 * nb8
     return BM
 
 
