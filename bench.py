@@ -63,12 +63,17 @@ def roofline_entry(nbytes, ops, seconds):
 
 
 def source_sha(*names):
-    """sha256 (16 hex digits) over the kernel sources a stored counter figure belongs to."""
+    """sha256 (16 hex digits) over the kernel sources a stored counter figure belongs to, comments and
+    white space left out (a reworded comment does not make a measurement stale)."""
+    import re
     h = hashlib.sha256()
     root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2412_14590_amd", "csrc")
     for n in names:
-        with open(os.path.join(root, n), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(root, n), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update("".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
@@ -273,18 +278,88 @@ def shape_sweep(args, torch, mx, synth, dev):
             "roofline": ref_row["roofline"], "rows": rows}
 
 
+def block_timeline(args, torch, mx, synth, dev):
+    """Where the blocks of the tiled kernel spend their time: needs a library built with
+    MIXLLM_EXTRA_FLAGS=-DMIXLLM_STAMPS (thread 0 of every block then records the 100 MHz clock at kernel
+    entry, after the prologue's loads have landed, after the K loop, after its drain, after the epilogue's
+    stores are issued and after they are acknowledged).  One layer (--layer of --model) at --m tokens,
+    single launches over >= 512 MB of rotating weight copies; medians over the launches of per-block means."""
+    import ctypes as C
+    lib = mx.lib()
+    if not hasattr(lib, "mixllm_debug_set_stamps"):
+        log("bench.py: --workload timeline needs a library built with MIXLLM_EXTRA_FLAGS=-DMIXLLM_STAMPS (set MIXLLM_LIB to it)")
+        sys.exit(2)
+    lib.mixllm_debug_set_stamps.argtypes = [C.c_void_p]
+    lib.mixllm_debug_set_stamps.restype = C.c_int
+    name, K, N, sigma, n_out = next(l for l in synth.model_layers(args.model) if l[0] == args.layer)
+    M = args.m if args.m is not None else 2048
+    path = {"auto": mx.PATH_PREFILL, "32": mx.PATH_PREFILL_32, "64": mx.PATH_PREFILL_64, "128": mx.PATH_PREFILL_128}[args.block_rows]
+    W = torch.from_numpy(synth.make_w(N, K, sigma, n_out, seed=0, tag="w/" + name)).to(dev)
+    n8 = synth.n8_for(N, 0.10)
+    L0 = mx.quantize_weights(W, torch.randperm(N, device=dev, generator=torch.Generator(device=dev).manual_seed(1))[:n8].to(torch.int32))
+    del W
+    n_c = max(2, -(-2 * MALL_BYTES // L0.weight_bytes()))
+    Ls = [L0] + [L0.clone() for _ in range(n_c - 1)]
+    x = torch.from_numpy(synth.make_x(M, K, seed=7, tag="x/" + name)).to(dev)
+    xq, xs = mx.quantize_activations(x)
+    y = torch.empty((M, N), dtype=torch.float16, device=dev)
+    ws = torch.empty(max(16, mx.query_sizes(M, K, N, n8)["linear_workspace_bytes"]), dtype=torch.uint8, device=dev)
+    # one row per block; an upper bound of the grid (smallest block shape, two partial column tiles, 8 K parts, padding to the XCDs)
+    n_rows = -(-M // 32) * (-(-N // 128) + 2) * 8 + 64
+    if n_rows > 1 << 20:
+        log("bench.py: --workload timeline: too many blocks for the stamp array")
+        sys.exit(2)
+    stamps = torch.zeros((n_rows, 8), dtype=torch.int64, device=dev)
+    for L in Ls:
+        mx.mixed_linear(xq, xs, L, path, out=y, workspace=ws)
+    torch.cuda.synchronize()
+    rows = []
+    for L in Ls * 2:
+        stamps.zero_()
+        torch.cuda.synchronize()
+        assert lib.mixllm_debug_set_stamps(stamps.data_ptr()) == 0
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        mx.mixed_linear(xq, xs, L, path, out=y, workspace=ws)
+        b.record()
+        torch.cuda.synchronize()
+        assert lib.mixllm_debug_set_stamps(None) == 0
+        st = stamps.cpu().numpy().astype(np.float64)
+        st = st[st[:, 5] > 0]
+        t0 = st[:, 0].min()
+        four, eight = st[st[:, 1] > 0], st[st[:, 1] == 0]      # only blocks of the 4-bit part carry the inner stamps
+        d = lambda i, j: float((four[:, i] - four[:, j]).mean()) / 100.0
+        rows.append([a.elapsed_time(b) * 1e3, len(st), d(1, 0), d(2, 1), d(3, 2), d(4, 3), d(5, 4), float(st[:, 5].max() - t0) / 100.0,
+                     float((eight[:, 5] - eight[:, 0]).mean()) / 100.0 if len(eight) else 0.0, len(eight)])
+    m = np.median(np.array(rows), axis=0)
+    keys = ["launch_us_by_events", "blocks", "prologue_us", "k_loop_us", "drain_and_last_rescale_us", "epilogue_issue_us", "store_ack_us",
+            "first_entry_to_last_exit_us", "entry_to_exit_of_an_8bit_block_us", "blocks_8bit"]
+    tl = {k: round(float(v), 2) for k, v in zip(keys, m)}
+    log(f"[timeline] {name} K={K} N={N} M={M} block rows {args.block_rows}: {json.dumps(tl)}")
+    ops = 2.0 * M * N * K
+    return {"metric": "mixed W4/W8-A8 linear TOPS + HBM GB/s at M=1..2048 (% roofline)", "value": ops / (tl["launch_us_by_events"] * 1e-6) / 1e12,
+            "unit": "TOP/s", "n_gpus": 1, "steps": 2 * n_c, "warmup": n_c, "ms_per_step": tl["launch_us_by_events"] * 1e-3, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+            "config": {"workload": f"single launches of the tiled kernel with clock stamps, layer {name} K={K} N={N}, M={M}, block rows {args.block_rows}",
+                       "library": os.environ.get("MIXLLM_LIB", "in-tree build")},
+            "timeline_of_a_4bit_block": tl}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=["decode", "prefill", "70b", "stack", "share-sweep", "salience", "shapes"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "prefill", "70b", "stack", "share-sweep", "salience", "shapes", "timeline"], default="decode",
                     help="decode / prefill: one Llama-3-8B-shaped block at M = 1 / 2048 (plus the other token counts as extra "
                          "legs); 70b: one Llama-3.1-70B-shaped block, M in {1, 16, 64, 256, 2048}; stack: 32 8B-shaped blocks "
                          "back to back with an uneven 8-bit share per layer, M in {1, 256}; share-sweep: single linears "
                          "K=4096, N in {4096, 14336}, 8-bit shares 0..100 %%, M = 1..1024 (the grid of the paper's "
                          "single-linear study, Sec. 5.2); salience: the global precision search of Sec. 3.2; shapes: every "
-                         "layer of a block (--model) x token counts (--ms) x kernel choice, the measurement behind the dispatch rules")
+                         "layer of a block (--model) x token counts (--ms) x kernel choice, the measurement behind the dispatch rules; "
+                         "timeline: clock stamps inside the blocks of the tiled kernel (needs a library built with -DMIXLLM_STAMPS)")
+    ap.add_argument("--layer", choices=["qkv", "o", "gate_up", "down"], default="gate_up", help="layer of --workload timeline")
+    ap.add_argument("--block-rows", choices=["auto", "32", "64", "128"], default="auto", help="token rows of a block in --workload timeline")
     ap.add_argument("--model", choices=["8b", "70b"], default="8b", help="layer shapes of --workload shapes")
     ap.add_argument("--ms", default="32,64,128,256,512", help="token counts of --workload shapes, comma separated")
     ap.add_argument("--m", type=int, default=None, help="tokens of the primary leg (default 1; 2048 for --workload prefill)")
@@ -311,6 +386,9 @@ def main():
         return
     if args.workload == "share-sweep":
         print(json.dumps(share_sweep(args, torch, mx, synth, dev)), flush=True)
+        return
+    if args.workload == "timeline":
+        print(json.dumps(block_timeline(args, torch, mx, synth, dev)))
         return
     if args.workload == "shapes":
         print(json.dumps(shape_sweep(args, torch, mx, synth, dev)), flush=True)

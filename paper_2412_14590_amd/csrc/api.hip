@@ -155,8 +155,10 @@ int hip_status(int e) { return e == (int)hipSuccess ? MIXLLM_OK : MIXLLM_EHIP; }
 // two paths the workload names.  Measured with every launch reading its weights from HBM (copies of
 // the layer rotating over 512 MB, as in a step of a model), on the Llama-shaped layers:
 //  * up to 32 tokens the weight-streaming kernel for a few dozen tokens (K = N = 4096: 11 against
-//    14.5 us for the tiled kernel), except on layers with a long K when the caller brings the
-//    scratch that lets the tiled kernel split K over blocks (K = 14336, N = 4096: 22 against 27 us);
+//    14 us for the tiled kernel), except on layers with a long K when the caller brings the
+//    scratch that lets the tiled kernel split K over blocks (K = 14336, N = 4096: 20 against 27 us),
+//    and on layers so wide that blocks of 32 x 128 fill the chip (K = 4096, N = 28672: 17 against
+//    18 us; K = 8192, N = 57344: 53-57 against 59-62 us);
 //  * from 33 tokens the tiled kernel with its small block shapes (K = N = 4096 at 64 tokens: 14.5
 //    against 15.4 us; K = 4096, N = 28672: 21 against 25 us; K = 8192, N = 57344: 67 against 81 us),
 //    except where its K loop is long, cannot be split for want of scratch, and the grid of 64 x 128
@@ -166,9 +168,10 @@ int auto_path(const mixllm_desc &d, const LinearParams &p)
     if (d.M <= 16) return MIXLLM_PATH_DECODE;
     if (d.M > 64 || !mid_covers(p)) return MIXLLM_PATH_PREFILL;
     const bool split = prefill_would_split(p);
-    if (d.M <= 32) return (split && p.ng > 64) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
     const long tiles = (long)(p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
-    return (p.ng < 64 || split || 4 * tiles >= 3L * cu_count()) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
+    const bool wide = 4 * tiles >= 3L * cu_count();   // column tiles of 128 channels for three quarters of the CUs or more
+    if (d.M <= 32) return ((split && p.ng > 64) || wide) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
+    return (p.ng < 64 || split || wide) ? MIXLLM_PATH_PREFILL : MIXLLM_PATH_MID;
 }
 
 // Which kernel a call takes: the caller's path argument with AUTO resolved, or a negative status

@@ -9,7 +9,9 @@
 //    so that the fragment reads of 16 consecutive lanes cover all 64 banks exactly once.
 //  * Packed weights (B operand, columns = channels) go L2 -> registers directly in the same
 //    packed layout the decode path streams: two 16-byte loads per lane fetch one group of a
-//    32-channel tile.  No weight byte passes through LDS.
+//    32-channel tile of 4-bit weights (requested one or two groups ahead), four one of 8-bit
+//    weights (three groups ahead, straight into a ring of operand registers).  No weight byte
+//    passes through LDS.
 //  * uint4 -> int8 unpack with zero-point subtraction in registers (step 1 of the two-step
 //    dequantization, Sec. 3.3), once per group per wave, reused by the TM token tiles; the
 //    unpack of group g+1 is spread over the second half of group g's MFMAs.
@@ -24,8 +26,10 @@
 //    block-wide barrier sits in the middle of a group (slot TM*2), where the next group's
 //    activations are known to have landed and the stage of the previous group is released.
 //  * Group metadata (4 fp16 scales, 4 zero points) is fetched once per 4 groups.
-//  * Epilogue: token scale, fp16 conversion, scatter to the original channel (Sec. 3.4).
-// 8-bit and 4-bit channel tiles are different block ranges of one launch.
+//  * Epilogue: token scale (all of a lane's scales requested by hand in one batch), fp16
+//    conversion, scatter to the original channel (Sec. 3.4).
+// 8-bit and 4-bit channel tiles are different block ranges of one launch; where the grid of output
+// tiles is short and K long, K is split over blocks and a second kernel adds the parts.
 #include <algorithm>
 #include <cstdlib>
 #include <mutex>
@@ -38,9 +42,10 @@ namespace mixllm {
 
 constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each)
 // Launch constants, each settable at build time for measurements (the values are the measured best):
-// groups between the request for packed 4-bit weights and the wait for them, by block shape.  One,
-// two or three groups ahead measure the same on every Llama-shaped layer from 64 to 2048 tokens
-// (the wait in the middle of a group is bound by the activations, not by the weights).
+// groups between the request for packed 4-bit weights and the wait for them, by block shape.  Two
+// and three groups ahead measure within 2 % of each other on every Llama-shaped layer from 64 to
+// 2048 tokens (the wait in the middle of a group is bound by the activations, which run two groups
+// ahead, not by the weights).
 #ifndef MIXLLM_PREFILL_WD_SMALL
 #define MIXLLM_PREFILL_WD_SMALL 2   // 32 x 128 and 64 x 128 blocks
 #endif
@@ -64,9 +69,9 @@ constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each
 #define MIXLLM_PREFILL_BAND 4
 #endif
 // waves (32 channels each) of the block with 128 token rows.  With 8 (blocks of 128 x 256, one per
-// CU, half the activation traffic through the L2s) the gate+up layer at 2048 tokens takes the same
-// time (339 against 338 us) and the layers of N <= 6144 up to 20 % longer (fewer, coarser blocks):
-// the kernel is not bound by its L2 traffic.
+// CU, half the activation traffic through the L2s) the gate+up layer at 2048 tokens takes 5 % longer
+// (336 against 319 us) and the layers of N <= 6144 10-20 % longer (fewer, coarser blocks): the
+// kernel is not bound by its L2 traffic.
 #ifndef MIXLLM_PREFILL_WN_LARGE
 #define MIXLLM_PREFILL_WN_LARGE 4
 #endif
@@ -985,7 +990,9 @@ bool prefill_covers(const LinearParams &p)
 // per part and output, so it is kept under 12 MB of sums.  Measured (Llama-3-8B down projection,
 // K = 14336, N = 4096): 58 -> 22 us at 32 tokens, 56 -> 23 at 64, 56 -> 34 at 128, 55 -> 46 at
 // 256; Llama-3.1-70B (K = 28672, N = 8192): 124 -> 46 at 32, 119 -> 88 at 128.  With K <= 4096
-// there is nothing to gain (a launch of 32 groups is 7 us of fixed cost plus 0.2 us per group).
+// there is nothing to gain: of the 14 us a 32 x 128 block of 32 groups lives, 4 us do not shrink with
+// K, more blocks per CU slow each other's groups down, and the adding kernel costs 4-5 us (K = N =
+// 4096 at 64 tokens: 14.5 us unsplit, 11.5 + 4.7 us in two parts, 11.6 + 4.7 us in four).
 // Returns the number of parts and, in qpp, their length in groups of 4 quantization groups.
 static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &qpp)
 {
@@ -1031,15 +1038,15 @@ int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
     p.kparts = 1;
     p.quads_per_part = (p.ng + 3) / 4;
     if (p.partials) p.kparts = choose_kparts(p, token_tiles_per_wave(p), p.partials_cap, p.quads_per_part);
-    // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 3 % slower).
+    // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 5 % slower).
     // Where that grid has clearly less than one block per CU the chip is short of waves, not of rate:
     // blocks of 64 x 128 (wave tile 64 x 32) or 32 x 128 (wave tile 32 x 32) double the waves and
-    // halve the chain of work each one runs; their packed weights are requested two groups ahead
-    // (a group is too short to cover the latency; on the large tile two groups ahead measured no gain).
-    // Measured on K = 4096, N = 4096 with hot weights, 128 x 128 -> the shape chosen here: 26.5 -> 15 us
-    // at M = 128, 27.7 -> 16.2 at M = 256, 29.1 -> 22.5 at M = 512; K = 14336: 72.1 -> 39.8, 74.7 -> 44.8,
-    // 78.0 -> 62.7.  With 192 blocks of 128 x 128 (N = 6144, M = 512) the smaller blocks are 4 % slower,
-    // with 224 (N = 28672, M = 128) equal.
+    // halve the chain of work each one runs; their packed 4-bit weights are requested two groups
+    // ahead (a group is too short to cover the latency).
+    // Measured on K = 4096, N = 4096, weights read from HBM at every launch, 128 x 128 -> the shape
+    // chosen here: 25.6 -> 14.1 us at M = 128, 25.7 -> 15.7 at M = 256, 26.2 -> 20.9 at M = 512; K = 14336
+    // (K not split): 76 -> 43, 76 -> 48, 76 -> 62.  With 192 blocks of 128 x 128 (N = 6144, M = 512) and
+    // with 224 (N = 28672, M = 128) the shapes are within 2 % of each other.
     switch (token_tiles_per_wave(p)) {
     case 1: return launch_shape<Shape<1, 4, 1, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
     case 2: return launch_shape<Shape<1, 4, 2, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
