@@ -294,8 +294,10 @@ int mixllm_debug_check_fast_division(uint64_t *mismatches, void *stream);
 
 /*
  * Test hook (host only, launches nothing): how a kernel of the given path would split the layer
- * of `d` over its blocks.  path = MIXLLM_PATH_DECODE_SPLIT: plan[0..3] = blocks of the 8-bit part,
- * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS;
+ * of `d` over its blocks.  path = MIXLLM_PATH_DECODE_SPLIT: plan[0..5] = blocks of the 8-bit part,
+ * blocks of the 4-bit part, virtual tiles covered by a block's LDS cells, bytes of LDS, windows over K
+ * the int8 activations are staged in (1 = the whole matrix at once), chunk columns (512 values of K)
+ * per window;
  * path = MIXLLM_PATH_MID: plan[0..4] = blocks of the 8-bit part, of the 4-bit part, quarter tiles
  * per virtual tile of the 8-bit and of the 4-bit part, bytes of LDS; path = MIXLLM_PATH_PREFILL:
  * plan[0..12] = token rows and channels of a block tile of the 4-bit part, its token tiles, channel

@@ -4,6 +4,11 @@ import re
 import subprocess
 import sys
 
+try:
+    from . import asm_scan
+except ImportError:   # run as a plain script
+    import asm_scan
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
@@ -97,6 +102,45 @@ def check_hand_issued_loads(asm_text: str, name: str) -> None:
         raise RuntimeError("registers of hand-issued loads are used before their wait:\n  " + "\n  ".join(bad[:10]))
 
 
+# Sources whose kernels pass the path-following scan of asm_scan.py (every path through the control-flow
+# graph, loop back edges included).  The others issue or await some loads under conditions the scan cannot
+# relate to each other (the same uniform test before the load and before its wait), which it reports as
+# paths without a wait; they get the straight-line scan above and the tripwire below.
+FULL_SCAN = {"linear_prefill.hip"}
+# Kernels that keep a ring of hand-issued loads in flight around a rolled loop: registers of the ring must
+# stay where they are.  Where the loop nest makes the compiler rotate them (seen with the chunk loop of
+# the evenly split decode kernel nested in a loop over activation windows: 80 to 220 copies, at the loop
+# latch, of registers whose loads were still in flight; the late data then landed in registers that
+# held addresses by then) the kernel has dozens of register-to-register copies of them; as built it
+# has none, or a handful that copy a thread index into a register the ring used earlier.
+RING_COPY_LIMIT = {"linear_decode_split.hip": ("linear_decode_split_kernel", 8)}
+
+
+def check_ring_copies(asm_text: str, src: str) -> None:
+    """Tripwire: count, per kernel, the VGPR-to-VGPR copies that name a destination register of a
+    hand-issued load of the ring (the activation loads are consumed before the loop and their
+    registers reused); fail above RING_COPY_LIMIT."""
+    kernel, limit = RING_COPY_LIMIT[src]
+    lines = asm_text.split("\n")
+    for st in [i for i, l in enumerate(lines) if re.match(r"^_Z\S*" + kernel + r"\S*:", l)]:
+        end = next((i for i in range(st, len(lines)) if "s_endpgm" in lines[i]), len(lines))
+        hand, copies, in_asm = set(), [], False
+        for l in lines[st:end]:
+            t = l.strip()
+            if t.startswith(";;#ASMSTART"):
+                in_asm = True
+            elif t.startswith(";;#ASMEND"):
+                in_asm = False
+            elif in_asm and (re.match(r"global_load_dwordx4 .* nt$", t) or t.startswith(("global_load_dwordx2", "global_load_ushort"))):
+                hand |= _vregs(t.split(",")[0])   # weights (non-temporal) and their scales and zero points: the ring
+            elif re.match(r"v_(mov_b(32|64)_e32|swap_b32) v[\[\d][^,]*, v[\[\d]", t):
+                copies.append(t)
+        n = sum(1 for c in copies if _vregs(c) & hand)
+        if n > limit:
+            raise RuntimeError(f"{lines[st].split(':')[0]}: {n} register copies of hand-loaded registers (limit {limit}): "
+                               "the compiler is moving a ring of loads that may be in flight")
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Objects are cached per source
     by modification time unless force is set."""
@@ -151,7 +195,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if pr.returncode != 0:
             raise RuntimeError(f"hipcc -S failed for {src}:\n{out}")
         try:
-            check_hand_issued_loads(open(a).read(), src)
+            text = open(a).read()
+            check_hand_issued_loads(text, src)
+            if src in FULL_SCAN:
+                asm_scan.check_hand_issued_loads(text, src)
+            if src in RING_COPY_LIMIT:
+                check_ring_copies(text, src)
         except RuntimeError:
             for stale in (a, os.path.join(objdir, src.replace(".hip", ".o"))):   # a later build must check again
                 if os.path.exists(stale):

@@ -153,7 +153,7 @@ int launch_linear_decode(const LinearParams &p, hipStream_t st);
 // evenly split decode variant
 int launch_linear_decode_split(const LinearParams &p, hipStream_t st);
 bool decode_split_covers(const LinearParams &p);
-bool decode_split_plan(const LinearParams &p, int out[4]);
+bool decode_split_plan(const LinearParams &p, int out[6]);
 bool mid_plan(const LinearParams &p, int out[5]);
 // Raise a kernel's dynamic-LDS limit (a per-function, per-device attribute; set once).  Returns a hipError_t.
 int ensure_dynamic_lds(const void *kernel, size_t bytes);

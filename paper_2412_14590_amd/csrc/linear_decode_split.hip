@@ -62,6 +62,11 @@ struct SplitArgs {
     int nblk8, nblk4;   // blocks of the 8-bit and of the 4-bit part
     uint32_t magic;     // ceil(2^32 / chunks per tile)
     int tcap;           // virtual tiles a block's LDS cells cover
+    // activation matrices beyond the LDS stage (WIN): K is walked in nwin windows of wq chunk
+    // columns (the last one may be shorter); magic_w, magic_l = ceil(2^32 / chunk columns) of a
+    // full window and of the last one
+    int nwin, wq;
+    uint32_t magic_w, magic_l;
 };
 
 template <int I, int N, typename F>
@@ -111,9 +116,16 @@ __device__ inline void await_vec(v4i &a)
 
 // FUSED: 0 = int8 codes and scales come from the stand-alone quantizer; 1 = one token of fp16
 // activations, 2 = several tokens of them (K a multiple of 512), quantized by every block for itself
-template <int NR, bool DUMP, bool ACT_PT, bool PART8, int FUSED>
+// WIN: the int8 activation matrix is larger than the LDS stage (5..16 tokens of a long K).  The block
+// then walks K in windows of at most 8192 values: its chunks are ordered window by window (inside
+// a window as before: virtual tile by virtual tile, wave w taking chunks w, w + 8, ...), the stage
+// holds one window at a time and is refilled between two barriers when every wave has finished
+// the window's chunks.  The ring of weight requests runs on across the refill; the LDS cells
+// collect a virtual tile's contributions over all windows.
+template <int NR, bool DUMP, bool ACT_PT, bool PART8, int FUSED, bool WIN>
 __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, uint8_t *smem)
 {
+    static_assert(!WIN || FUSED == 0, "windows are for int8 activations from the stand-alone quantizer");
     // Chunk requests: R chunks are requested before the first one is consumed - E of them in the
     // same instant as the activations, the others as soon as the activations have landed, so that
     // the memory system has work while the block quantizes and stages them - and from then on one
@@ -135,7 +147,9 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     const int ng = p.ng, ngp = p.ngp;
     const int nquads = (ng + 3) / 4;
     const bool per_group_s8 = PART8 && !p.w8_per_channel;
-    const int xstride = p.K + A_PAD;
+    const int wq = WIN ? a.wq : nquads, nwin = WIN ? a.nwin : 1;   // chunk columns of a window, windows
+    const int wql = nquads - (nwin - 1) * wq;                       // chunk columns of the last window
+    const int xstride = (WIN ? wq * 4 * G : p.K) + A_PAD;
 
     // ---- the block's virtual tiles, the wave's chunks ----
     // Full rounds: virtual tile t of block b is packed tile b + nblk t, so that at any moment the
@@ -150,8 +164,30 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     const int L_lo = (int)(left * (unsigned)b / (unsigned)nblk), L_hi = (int)(left * (unsigned)(b + 1) / (unsigned)nblk);   // L_hi - L_lo <= 4
     const int nvt = rounds + (L_hi > L_lo ? 1 : 0);   // >= 1: the host never launches more blocks than quarter tiles
     const int n = nvt * nquads;                       // chunks of the block
-    const int n_my = wave < n ? (n - wave + NW - 1) / NW : 0;
+    auto share = [&](int chunks) { return wave < chunks ? (chunks - wave + NW - 1) / NW : 0; };
+    const int cnt_w = WIN ? share(nvt * wq) : 0, cnt_l = WIN ? share(nvt * wql) : 0;   // this wave's chunks in a full window, in the last one
+    const int n_my = WIN ? (nwin - 1) * cnt_w + cnt_l : share(n);
     auto vtile_of = [&](int j) { return nquads == 1 ? j : (int)__umulhi((unsigned)j, a.magic); };
+    // chunk i of this wave's list: its virtual tile, its chunk column in K and (WIN) its window
+    auto locate = [&](int i, int &vt, int &q, int &win) {
+        if (!WIN) {
+            const int j = wave + NW * i;
+            vt = vtile_of(j);
+            q = j - vt * nquads;
+            win = 0;
+        } else {
+            win = 0;
+            while (win < nwin - 1 && i >= cnt_w) {
+                i -= cnt_w;
+                ++win;
+            }
+            const int j = wave + NW * i;
+            const bool lastw = win == nwin - 1;
+            const int cols = lastw ? wql : wq;
+            vt = cols == 1 ? j : (int)__umulhi((unsigned)j, lastw ? a.magic_l : a.magic_w);
+            q = win * wq + (j - vt * cols);
+        }
+    };
 
     // ---- LDS ----
     float *wmax = (float *)smem;                                     // [NW] row maxima (built-in quantizer)
@@ -178,8 +214,8 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     // loads is issued (the waits count them), all lanes reading the first bytes of the share
     auto issue = [&](int i, Slot<PART8> &k) {
         const bool real = i < n_my;
-        const int j = real ? wave + NW * i : 0;
-        const int vt = vtile_of(j), q = j - vt * nquads;
+        int vt = 0, q = 0, win = 0;   // (a dummy request reads the first bytes of the share)
+        if (real) locate(i, vt, q, win);
         const int g0 = 4 * q;
         const int last = ng - 1 - g0;   // at the ragged end of K the last group is re-read (its scale is forced to zero)
         int base_tile;
@@ -209,9 +245,30 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     v4i xv[MAXV];
     const int npiece = FUSED ? p.M * (p.K / 8) : p.M * (p.K / 16);   // 16-byte pieces of the activation matrix
     const void *xsrc = FUSED ? (const void *)p.x : (const void *)p.xq;
+    // WIN: load j of a thread is its piece of token row j (a window's row has at most NT pieces;
+    // threads beyond the row's end read its last piece again and store nothing)
+    // 16-byte pieces of a token row that window win holds (the last chunk column may reach past K)
+    auto window_pieces = [&](int win) { return min((win == nwin - 1 ? wql : wq) * (4 * G / 16), (p.K - win * wq * 4 * G) / 16); };
+    auto request_window = [&](int win) {
+        const int pieces = window_pieces(win);
+        const uint32_t col = (uint32_t)(win * wq * 4 * G + min(tid, pieces - 1) * 16);
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j)
-        if (j * NT < npiece) load_reg16<0>(xv[j], (uint32_t)min(tid + NT * j, npiece - 1) * 16u, xsrc);
+        for (int j = 0; j < MAXV; ++j)
+            if (j < p.M) load_reg16<0>(xv[j], (uint32_t)j * (uint32_t)p.K + col, xsrc);
+    };
+    auto store_window = [&](int win) {
+        const int pieces = window_pieces(win);
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j)
+            if (j < p.M && tid < pieces) *(v4i *)(lds_x + j * xstride + tid * 16) = xv[j];
+    };
+    if (WIN) {
+        request_window(0);
+    } else {
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j)
+            if (j * NT < npiece) load_reg16<0>(xv[j], (uint32_t)min(tid + NT * j, npiece - 1) * 16u, xsrc);
+    }
     Slot<PART8> ring[R];
     sfor<0, E>([&](auto dc) { issue(decltype(dc)::value, ring[decltype(dc)::value]); });   // always E chunks, past the end of the list dummy ones (the staging waits count them)
     // the output channel and token scales of the first virtual tile this wave will finish:
@@ -241,7 +298,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     }
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
-        if (j * NT < npiece) await_vec<E * NL>(xv[j]);
+        if (WIN ? j < p.M : j * NT < npiece) await_vec<E * NL>(xv[j]);
     sfor<E, R>([&](auto dc) {   // the rest of the first R chunks, where the wave's list has them
         if (decltype(dc)::value < n_my) issue(decltype(dc)::value, ring[decltype(dc)::value]);
     });
@@ -355,6 +412,8 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
         }
 #pragma unroll
         for (int r = 0; r < NR; ++r) xs_tok[r] = sc;
+    } else if (WIN) {
+        store_window(0);
     } else {
         const int per_row = p.K / 16;
 #pragma unroll
@@ -370,8 +429,9 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     const int8_t *arow = lds_x + tok_a * xstride + ks * 16;
     const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
     auto compute = [&](int i, const Slot<PART8> &k) {
-        const int j = wave + NW * i;
-        const int vt = vtile_of(j), q = j - vt * nquads;
+        int vt, q, win;
+        locate(i, vt, q, win);
+        const int8_t *awin = arow - (WIN ? win * wq * 4 * G : 0);   // the stage holds the window's columns only
         // The four fp16 scales are taken out of the two loaded dwords with integer operations
         // only: a reinterpreting copy of k.s makes the compiler keep k.s as 16-bit pieces, and
         // it then splits the dwords right after the load is issued, before the data is there.
@@ -393,7 +453,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
             const int g = 4 * q + u;
             const bool gvalid = g < ng;
             const int gc = min(g, ng - 1);
-            const v4i a0 = *(const v4i *)(arow + gc * G), a1 = *(const v4i *)(arow + gc * G + 64);
+            const v4i a0 = *(const v4i *)(awin + gc * G), a1 = *(const v4i *)(awin + gc * G + 64);
             v4i P;
             float sw;
             if (PART8) {
@@ -438,6 +498,25 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
             for (int r = 0; r < NR; ++r) red[((vt * NW + wave) * NR + r) * 64 + lane] += acc[r];
         }
     };
+    // WIN: the window the stage holds and the end of its chunks in this wave's list.  When the wave
+    // comes to a chunk of a later window (or to the end of its list) it requests the next window, waits
+    // for ALL of its loads (the chunk requests in flight are older and land first) and stores the
+    // window once every wave has finished with the present one.  The window's registers are live only
+    // here: held across the chunk loop (requested a window ahead) they are written on several paths,
+    // and the compiler then keeps them in two sets of registers and copies one to the other where the
+    // paths meet, while the loads are in flight.
+    int win_now = 0, win_end = nwin == 1 ? cnt_l : cnt_w;
+    auto next_window = [&]() {
+        ++win_now;
+        win_end += win_now == nwin - 1 ? cnt_l : cnt_w;
+        request_window(win_now);
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j)
+            if (j < p.M) await_vec<0>(xv[j]);
+        lds_barrier();   // every wave has read the last of the window before
+        store_window(win_now);
+        lds_barrier();
+    };
     for (int i0 = 0; i0 < n_my; i0 += R) {
         sfor<0, R>([&](auto dc) {
             constexpr int d = decltype(dc)::value;
@@ -448,6 +527,10 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
                 // left.  Nothing is requested past the end of the list, so the last wait leaves
                 // nothing in flight.
                 if (i >= R - 1 && i + 1 < n_my) issue(i + 1, ring[(d + 1) % R]);
+                // (after the request, so that the ring is not empty when the wave comes out of the
+                // change of window; the waits below then find everything landed)
+                if (WIN)
+                    while (i >= win_end) next_window();   // (a wave may have no chunk in a window)
                 const int younger = i < R - 1 ? primed - 1 - i : (i + 1 < n_my ? 1 : 0);   // chunks requested after chunk i
                 sfor<0, R>([&](auto yc) {
                     constexpr int y = decltype(yc)::value;
@@ -458,6 +541,8 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
             }
         });
     }
+    if (WIN)
+        while (win_now < nwin - 1) next_window();   // every wave passes every window's barriers
     // nothing may still be on its way into a register when the registers get other uses
     sfor<0, R>([&](auto dc) { await_slot<0>(ring[decltype(dc)::value]); });
     if (DUMP) return;
@@ -483,20 +568,21 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     }
 }
 
-template <int NR, bool DUMP, bool ACT_PT, int FUSED>
+template <int NR, bool DUMP, bool ACT_PT, int FUSED, bool WIN = false>
 __global__ __launch_bounds__(NT) void linear_decode_split_kernel(LinearParams p, SplitArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     if ((int)blockIdx.x < a.nblk8)
-        split_block<NR, DUMP, ACT_PT, true, FUSED>(p, a, smem);
+        split_block<NR, DUMP, ACT_PT, true, FUSED, WIN>(p, a, smem);
     else
-        split_block<NR, DUMP, ACT_PT, false, FUSED>(p, a, smem);
+        split_block<NR, DUMP, ACT_PT, false, FUSED, WIN>(p, a, smem);
 }
 
 // ---- host side ------------------------------------------------------------------------------
 
 struct Plan {
     int nblk8, nblk4, tcap, nr;
+    int nwin, wq;   // windows over K and chunk columns per window (nwin = 1: the whole matrix is staged once)
     size_t lds_bytes;
 };
 
@@ -533,12 +619,42 @@ bool compute_plan(const LinearParams &p, Plan &o)
     // (52.2 against 52.7 us per step at M = 4), 32 Ki values much more (68.0 against 57.7 at M = 8).
     if (fused && (p.P || (size_t)p.M * p.K > (size_t)NT * 8 * 4)) return false;
     if (fused && p.act_per_token && p.M > 1 && p.K % 512 != 0) return false;
-    if (!fused && (size_t)p.M * p.K > (size_t)NT * 16 * 16) return false;
+    // int8 activations beyond 16 loads of 16 bytes per thread are staged window by window (built for
+    // 5..16 tokens)
+    const bool windows = !fused && (size_t)p.M * p.K > (size_t)NT * 16 * 16;
+    if (windows && (p.M <= 4 || (size_t)p.M * p.K >= ((size_t)1 << 31))) return false;
     o.nr = p.M <= 4 ? 1 : 4;
+    o.nwin = 1;
     const int nquads = (p.ng + 3) / 4;
+    o.wq = nquads;
     const long long units8 = 4ll * p.ntiles8, units4 = 4ll * p.ntiles4;
     if (units8 + units4 == 0 || std::max(units8, units4) * MAX_BLOCKS >= (1ll << 31)) return false;
-    const size_t fixed = LDS_HEADER + (p.act_per_token ? 0 : ((size_t)p.M * p.ng + 3) / 4 * 16) + (size_t)p.M * (p.K + A_PAD);
+    const size_t scales = LDS_HEADER + (p.act_per_token ? 0 : ((size_t)p.M * p.ng + 3) / 4 * 16);
+    if (windows) {
+        // one block per CU; the widest window (in chunk columns: 16 = 8192 values, a row of NT
+        // pieces) that fits next to the cells - multiples of 8 keep the waves' shares of a window even
+        const int nb = cu_count();
+        int nblk8 = 0, nblk4 = 0;
+        split_blocks((int)units8, (int)units4, nb, nblk8, nblk4);
+        int share = 1;
+        if (nblk8) share = std::max(share, ceil_div((int)units8, nblk8));
+        if (nblk4) share = std::max(share, ceil_div((int)units4, nblk4));
+        const int tcap = ceil_div(share, 4) + 1;
+        if ((long long)tcap * nquads * nquads >= (1ll << 31)) return false;
+        for (int wq : {16, 12, 8, 4, 2, 1}) {
+            const size_t lds = scales + (size_t)p.M * (wq * 4 * G + A_PAD) + (size_t)tcap * NW * o.nr * 256;
+            if (lds > LDS_LIMIT) continue;
+            o.nblk8 = nblk8;
+            o.nblk4 = nblk4;
+            o.tcap = tcap;
+            o.wq = wq;
+            o.nwin = ceil_div(nquads, wq);
+            o.lds_bytes = lds;
+            return o.nwin >= 2;   // (a matrix of more than 128 KB never fits one window)
+        }
+        return false;
+    }
+    const size_t fixed = scales + (size_t)p.M * (p.K + A_PAD);
     for (int nb = cu_count(); nb <= MAX_BLOCKS; nb *= 2) {
         // every block stages the whole activation matrix: with more than 64 KB of it, more than one
         // block per CU costs more than it gains (the kernel for a few dozen tokens takes those shapes)
@@ -601,6 +717,14 @@ int launch_nr(const LinearParams &p, const SplitArgs &a, size_t lds_bytes, hipSt
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p, a);
         return (int)hipGetLastError();
     };
+    if (a.nwin > 1) {   // activations staged window by window
+        if constexpr (NR == 4) {
+            if (p.P) return go(linear_decode_split_kernel<4, true, true, 0, true>);
+            if (p.act_per_token) return go(linear_decode_split_kernel<4, false, true, 0, true>);
+            return go(linear_decode_split_kernel<4, false, false, 0, true>);
+        }
+        return (int)hipErrorInvalidValue;
+    }
     if (p.P) return go(linear_decode_split_kernel<NR, true, true, 0>);
     if (p.x && !p.act_per_token) return go(linear_decode_split_kernel<NR, false, false, 2>);
     if (p.x && p.M > 1) return go(linear_decode_split_kernel<NR, false, true, 2>);
@@ -620,9 +744,10 @@ bool decode_split_covers(const LinearParams &p)
     return make_plan(p, pl);
 }
 
-// the launch plan as four integers (blocks of the 8-bit part, of the 4-bit part, virtual tiles an
-// LDS cell area covers, bytes of LDS), for the host-side test of the work split
-bool decode_split_plan(const LinearParams &p, int out[4])
+// the launch plan as six integers (blocks of the 8-bit part, of the 4-bit part, virtual tiles an
+// LDS cell area covers, bytes of LDS, windows the activations are staged in, chunk columns - 512
+// values of K - per window), for the host-side test of the work split
+bool decode_split_plan(const LinearParams &p, int out[6])
 {
     Plan pl;
     if (!make_plan(p, pl)) return false;
@@ -630,6 +755,8 @@ bool decode_split_plan(const LinearParams &p, int out[4])
     out[1] = pl.nblk4;
     out[2] = pl.tcap;
     out[3] = (int)pl.lds_bytes;
+    out[4] = pl.nwin;
+    out[5] = pl.wq;
     return true;
 }
 
@@ -643,6 +770,11 @@ int launch_linear_decode_split(const LinearParams &p, hipStream_t st)
     const int nquads = (p.ng + 3) / 4;
     a.magic = nquads == 1 ? 0u : (uint32_t)(((1ull << 32) + nquads - 1) / nquads);
     a.tcap = pl.tcap;
+    a.nwin = pl.nwin;
+    a.wq = pl.wq;
+    const int wql = nquads - (pl.nwin - 1) * pl.wq;
+    a.magic_w = (uint32_t)(((1ull << 32) + pl.wq - 1) / pl.wq);   // (unused where a window has one chunk column)
+    a.magic_l = (uint32_t)(((1ull << 32) + wql - 1) / wql);
     return pl.nr == 1 ? launch_nr<1>(p, a, pl.lds_bytes, st) : launch_nr<4>(p, a, pl.lds_bytes, st);
 }
 

@@ -29,8 +29,9 @@ def say(*a):
 
 
 def split_variant_covers(M, K):
-    """The evenly split decode variant stages the whole int8 activation matrix in LDS."""
-    return M <= 16 and M * K <= 131072
+    """The evenly split decode variant stages the int8 activation matrix in LDS: whole up to 128 Ki values,
+    beyond that (built for 5..16 tokens) in windows over K."""
+    return M <= 16 and (M * K <= 131072 or M >= 5)
 
 
 def skip_unless_covered(path, M, K):
@@ -191,7 +192,10 @@ def check_partials(M, K, N, n8, path, seed=24):
 
 
 @pytest.mark.parametrize("M,K,N,n8", [(3, 256, 7, 2), (16, 1024, 100, 9), (1, 4096, 300, 30), (9, 640, 50, 0),
-                                     (5, 384, 40, 40), (2, 2048, 2070, 207), (4, 14336, 100, 12), (4, 28672, 48, 5)])
+                                     (5, 384, 40, 40), (2, 2048, 2070, 207), (4, 14336, 100, 12), (4, 28672, 48, 5),
+                                     # more than 128 Ki activation values: the split variant walks K in windows
+                                     # (14336: 16 + 12 chunk columns; 9088: 16 + 2, the last group alone in its chunk)
+                                     (16, 14336, 100, 12), (9, 28672, 48, 5), (15, 9088, 70, 7)])
 @pytest.mark.parametrize("path", ["generic", "decode"] + DECODE_VARIANTS)
 def test_group_partials_bit_exact_small_m(M, K, N, n8, path):
     say("partials", path, M, K, N, n8)
@@ -273,7 +277,9 @@ def check_linear(M, K, N, n8, path, variant="baseline", seed=25):
 @pytest.mark.parametrize("path", ["generic", "decode"] + DECODE_VARIANTS)
 @pytest.mark.parametrize("M,K,N,n8", [(1, 4096, 4096, 410), (16, 1024, 100, 9), (4, 640, 50, 0), (7, 384, 40, 40),
                                      (8, 14336, 272, 27), (3, 128, 33, 3), (2, 2048, 2070, 207), (1, 14336, 1000, 90),
-                                     (4, 28672, 48, 5), (3, 32768, 40, 4)])
+                                     (4, 28672, 48, 5), (3, 32768, 40, 4),
+                                     # the split variant with the activations staged window by window
+                                     (16, 14336, 272, 27), (10, 14336, 1000, 0), (16, 9088, 70, 70), (6, 28672, 48, 5)])
 def test_linear_small_m(M, K, N, n8, path, variant):
     skip_unless_covered(path, M, K)
     check_linear(M, K, N, n8, path, variant)

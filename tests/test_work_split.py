@@ -87,6 +87,32 @@ def check_mid_part(ntiles, nblk, qv):
     assert len(seen) == 16 * ntiles
 
 
+def check_windowed_chunk_lists(nvt, nquads, nwin, wq):
+    """linear_decode_split.hip, activations staged window by window: the eight waves' chunk lists, located the
+    way the kernel does it (window by subtraction, virtual tile by multiplication with ceil(2^32 / columns)),
+    visit every (virtual tile, chunk column) once, every chunk inside the window its wave is in."""
+    wql = nquads - (nwin - 1) * wq
+    assert 1 <= wql <= wq
+    magic = {c: ((1 << 32) + c - 1) // c for c in (wq, wql)}
+    seen = set()
+    for wave in range(8):
+        share = lambda chunks: (chunks - wave + 7) // 8 if wave < chunks else 0
+        cnt_w, cnt_l = share(nvt * wq), share(nvt * wql)
+        for i in range((nwin - 1) * cnt_w + cnt_l):
+            win, ii = 0, i
+            while win < nwin - 1 and ii >= cnt_w:
+                ii -= cnt_w
+                win += 1
+            j = wave + 8 * ii
+            cols = wql if win == nwin - 1 else wq
+            vt = j if cols == 1 else (j * magic[cols]) >> 32
+            q = win * wq + (j - vt * cols)
+            assert vt == j // cols and 0 <= vt < nvt and win * wq <= q < min(nquads, (win + 1) * wq)
+            assert (vt, q) not in seen
+            seen.add((vt, q))
+    assert len(seen) == nvt * nquads
+
+
 SHAPES = [(28672, 8192, 819), (4096, 4096, 410), (4096, 6144, 614), (4096, 28672, 2867), (14336, 4096, 410), (8192, 10240, 1024),
           (8192, 57344, 5734), (256, 7, 2), (384, 70, 70), (1024, 530, 0), (640, 50, 5), (128, 16, 16), (512, 4097, 1),
           (4096, 14336, 10178), (2048, 2070, 207), (128, 33, 3)]
@@ -95,17 +121,25 @@ SHAPES = [(28672, 8192, 819), (4096, 4096, 410), (4096, 6144, 614), (4096, 28672
 @pytest.mark.parametrize("K,N,n8", SHAPES)
 def test_decode_split_plan_covers_every_channel_once(K, N, n8):
     t8, t4 = tiles(N, n8)
-    for M in (1, 4, 5, 16):
+    for M in (1, 4, 5, 9, 12, 16):
         rc, p = plan(mx.PATH_DECODE_SPLIT, M, K, N, n8)
-        if M * K > 131072:
+        if M * K > 131072 and M <= 4:
             assert rc == -2            # the activations do not fit the LDS stage: not covered, not an error path
             continue
         if rc == -2:                   # fits, but only with several blocks per CU each staging > 64 KB
-            assert M * K > 65536
+            assert 65536 < M * K <= 131072
             continue
         assert rc == 0, (M, K, N, n8)
-        nblk8, nblk4, tcap, lds = p[:4]
+        nblk8, nblk4, tcap, lds, nwin, wq = p[:6]
         assert lds <= 160 * 1024
+        nquads = (K // 128 + 3) // 4
+        if M * K > 131072:             # staged window by window: one block per CU, a window's row is at most 512 pieces
+            assert nblk8 + nblk4 <= 256 and wq in (16, 12, 8, 4, 2, 1) and nwin == -(-nquads // wq) >= 2
+            assert lds >= M * (wq * 512 + 16) + tcap * 8 * 4 * 256
+            for nvt in range(1, tcap + 1):
+                check_windowed_chunk_lists(nvt, nquads, nwin, wq)
+        else:
+            assert (nwin, wq) == (1, nquads)
         check_decode_split_part(t8, nblk8, tcap)
         check_decode_split_part(t4, nblk4, tcap)
 
