@@ -117,11 +117,12 @@ __device__ inline void await_vec(v4i &a)
 // FUSED: 0 = int8 codes and scales come from the stand-alone quantizer; 1 = one token of fp16
 // activations, 2 = several tokens of them (K a multiple of 512), quantized by every block for itself
 // WIN: the int8 activation matrix is larger than the LDS stage (5..16 tokens of a long K).  The block
-// then walks K in windows of at most 8192 values: its chunks are ordered window by window (inside
-// a window as before: virtual tile by virtual tile, wave w taking chunks w, w + 8, ...), the stage
-// holds one window at a time and is refilled between two barriers when every wave has finished
-// the window's chunks.  The ring of weight requests runs on across the refill; the LDS cells
-// collect a virtual tile's contributions over all windows.
+// then walks K in windows: its chunks are ordered window by window (inside a window as before:
+// virtual tile by virtual tile, wave w taking chunks w, w + 8, ...), and the stage is two buffers,
+// one holding the window being read, the other being filled with the next one by loads that write
+// straight to LDS (no registers), requested a whole window ahead.  A change of window is one barrier.
+// The ring of weight requests runs on across it; the LDS cells collect a virtual tile's
+// contributions over all windows.
 template <int NR, bool DUMP, bool ACT_PT, bool PART8, int FUSED, bool WIN>
 __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, uint8_t *smem)
 {
@@ -245,22 +246,28 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     v4i xv[MAXV];
     const int npiece = FUSED ? p.M * (p.K / 8) : p.M * (p.K / 16);   // 16-byte pieces of the activation matrix
     const void *xsrc = FUSED ? (const void *)p.x : (const void *)p.xq;
-    // WIN: load j of a thread is its piece of token row j (a window's row has at most NT pieces;
-    // threads beyond the row's end read its last piece again and store nothing)
-    // 16-byte pieces of a token row that window win holds (the last chunk column may reach past K)
-    auto window_pieces = [&](int win) { return min((win == nwin - 1 ? wql : wq) * (4 * G / 16), (p.K - win * wq * 4 * G) / 16); };
+    // WIN: window win goes to buffer win & 1, row by row in pieces of 1 KB (one load instruction of
+    // a wave: lane l writes 16 bytes at the piece's address + 16 l); the pieces of a window are dealt
+    // round robin to the waves.  Lanes past the end of K read the row's last 16 bytes again, into
+    // columns that no chunk reads.
+    const int xbuf = p.M * xstride;
     auto request_window = [&](int win) {
-        const int pieces = window_pieces(win);
-        const uint32_t col = (uint32_t)(win * wq * 4 * G + min(tid, pieces - 1) * 16);
-#pragma unroll
-        for (int j = 0; j < MAXV; ++j)
-            if (j < p.M) load_reg16<0>(xv[j], (uint32_t)j * (uint32_t)p.K + col, xsrc);
-    };
-    auto store_window = [&](int win) {
-        const int pieces = window_pieces(win);
-#pragma unroll
-        for (int j = 0; j < MAXV; ++j)
-            if (j < p.M && tid < pieces) *(v4i *)(lds_x + j * xstride + tid * 16) = xv[j];
+        const int segs = ((win == nwin - 1 ? wql : wq) + 1) / 2;   // pieces per row
+        const uint32_t dst0 = lds_address(lds_x) + (uint32_t)((win & 1) * xbuf);
+        int row = 0, seg = wave;   // piece t = wave + NW k as (row, piece of the row)
+        while (seg >= segs) {
+            seg -= segs;
+            ++row;
+        }
+        while (row < p.M) {
+            const uint32_t col = (uint32_t)min(win * wq * 4 * G + seg * 1024 + lane * 16, p.K - 16);
+            load_lds16(dst0 + (uint32_t)(row * xstride + seg * 1024), (uint32_t)row * (uint32_t)p.K + col, p.xq);
+            seg += NW;
+            while (seg >= segs) {
+                seg -= segs;
+                ++row;
+            }
+        }
     };
     if (WIN) {
         request_window(0);
@@ -296,9 +303,13 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
         if (tid < 16) tokmax[tid] = 0u;
         lds_barrier();   // while the activations are still on their way
     }
+    if (WIN) {
+        await_loads<E * NL>();               // the first window has landed (this wave's part of it)
+        if (nwin > 1) request_window(1);     // (ahead of the chunk requests that follow, as at every change of window)
+    }
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
-        if (WIN ? j < p.M : j * NT < npiece) await_vec<E * NL>(xv[j]);
+        if (!WIN && j * NT < npiece) await_vec<E * NL>(xv[j]);
     sfor<E, R>([&](auto dc) {   // the rest of the first R chunks, where the wave's list has them
         if (decltype(dc)::value < n_my) issue(decltype(dc)::value, ring[decltype(dc)::value]);
     });
@@ -412,9 +423,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
         }
 #pragma unroll
         for (int r = 0; r < NR; ++r) xs_tok[r] = sc;
-    } else if (WIN) {
-        store_window(0);
-    } else {
+    } else if (!WIN) {
         const int per_row = p.K / 16;
 #pragma unroll
         for (int j = 0; j < MAXV; ++j) {
@@ -431,7 +440,7 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
     auto compute = [&](int i, const Slot<PART8> &k) {
         int vt, q, win;
         locate(i, vt, q, win);
-        const int8_t *awin = arow - (WIN ? win * wq * 4 * G : 0);   // the stage holds the window's columns only
+        const int8_t *awin = arow + (WIN ? (win & 1) * xbuf - win * wq * 4 * G : 0);   // the window's buffer holds its columns only
         // The four fp16 scales are taken out of the two loaded dwords with integer operations
         // only: a reinterpreting copy of k.s makes the compiler keep k.s as 16-bit pieces, and
         // it then splits the dwords right after the load is issued, before the data is there.
@@ -498,51 +507,56 @@ __device__ inline void split_block(const LinearParams &p, const SplitArgs &a, ui
             for (int r = 0; r < NR; ++r) red[((vt * NW + wave) * NR + r) * 64 + lane] += acc[r];
         }
     };
-    // WIN: the window the stage holds and the end of its chunks in this wave's list.  When the wave
-    // comes to a chunk of a later window (or to the end of its list) it requests the next window, waits
-    // for ALL of its loads (the chunk requests in flight are older and land first) and stores the
-    // window once every wave has finished with the present one.  The window's registers are live only
-    // here: held across the chunk loop (requested a window ahead) they are written on several paths,
-    // and the compiler then keeps them in two sets of registers and copies one to the other where the
-    // paths meet, while the loads are in flight.
+    // WIN: the window being read and the end of its chunks in this wave's list.  The window after it
+    // was requested when this one became the present one.  When the wave comes to a chunk of a later
+    // window (or to the end of its list) it waits for all of its loads - its part of the next window,
+    // long landed, and the chunk it is about to consume; the request for the chunk after that is held
+    // back until after the change - meets the other waves, who have then all finished with the
+    // present window and landed their parts of the next, and requests the window after the next
+    // into the buffer that has become free.  Those loads stand in the queue BEFORE the next chunk
+    // request: a wait for that chunk then covers them at no cost (they come from L2 and were made
+    // at the same time), whereas behind it every later wait would count them as younger loads and
+    // the immediate counts of the waits would have to know how many there are.
+    constexpr int XLMAX = 16;   // loads of a window per wave at most (16 rows of 8 KB in pieces of 1 KB over 8 waves)
     int win_now = 0, win_end = nwin == 1 ? cnt_l : cnt_w;
     auto next_window = [&]() {
+        await_loads<0>();
+        lds_barrier();
         ++win_now;
         win_end += win_now == nwin - 1 ? cnt_l : cnt_w;
-        request_window(win_now);
-#pragma unroll
-        for (int j = 0; j < MAXV; ++j)
-            if (j < p.M) await_vec<0>(xv[j]);
-        lds_barrier();   // every wave has read the last of the window before
-        store_window(win_now);
-        lds_barrier();
+        if (win_now + 1 < nwin) request_window(win_now + 1);
     };
     for (int i0 = 0; i0 < n_my; i0 += R) {
         sfor<0, R>([&](auto dc) {
             constexpr int d = decltype(dc)::value;
             const int i = i0 + d;
             if (i < n_my) {
+                bool landed = false;   // (a change of window has waited for chunk i as well)
+                if (WIN) {
+                    while (i >= win_end) {   // (more than once where the wave has no chunk in a window)
+                        next_window();
+                        landed = true;
+                    }
+                }
                 // The first `primed` chunks were requested at the start; from chunk R - 1 on, chunk
                 // i + 1 is requested before chunk i is awaited, into the slot chunk i + 1 - R has
                 // left.  Nothing is requested past the end of the list, so the last wait leaves
                 // nothing in flight.
                 if (i >= R - 1 && i + 1 < n_my) issue(i + 1, ring[(d + 1) % R]);
-                // (after the request, so that the ring is not empty when the wave comes out of the
-                // change of window; the waits below then find everything landed)
-                if (WIN)
-                    while (i >= win_end) next_window();   // (a wave may have no chunk in a window)
                 const int younger = i < R - 1 ? primed - 1 - i : (i + 1 < n_my ? 1 : 0);   // chunks requested after chunk i
-                sfor<0, R>([&](auto yc) {
-                    constexpr int y = decltype(yc)::value;
-                    if (younger == y) await_loads<y * NL>();
-                });
-                await_slot<(R - 1) * NL>(ring[d]);   // ties the registers to the wait above (its own wait is the weakest of them)
+                if (!landed) {
+                    sfor<0, R>([&](auto yc) {
+                        constexpr int y = decltype(yc)::value;
+                        if (younger == y) await_loads<y * NL>();
+                    });
+                }
+                await_slot<(R - 1) * NL + (WIN ? XLMAX : 0)>(ring[d]);   // ties the registers to the wait above (its own wait is the weakest of them)
                 compute(i, ring[d]);
             }
         });
     }
     if (WIN)
-        while (win_now < nwin - 1) next_window();   // every wave passes every window's barriers
+        while (win_now < nwin - 1) next_window();   // every wave passes every window's barrier
     // nothing may still be on its way into a register when the registers get other uses
     sfor<0, R>([&](auto dc) { await_slot<0>(ring[decltype(dc)::value]); });
     if (DUMP) return;
@@ -631,18 +645,18 @@ bool compute_plan(const LinearParams &p, Plan &o)
     if (units8 + units4 == 0 || std::max(units8, units4) * MAX_BLOCKS >= (1ll << 31)) return false;
     const size_t scales = LDS_HEADER + (p.act_per_token ? 0 : ((size_t)p.M * p.ng + 3) / 4 * 16);
     if (windows) {
-        // one block per CU; the widest window (in chunk columns: 16 = 8192 values, a row of NT
-        // pieces) that fits next to the cells - multiples of 8 keep the waves' shares of a window even
+        // one block per CU; two buffers of the widest window (in chunk columns of 512 values) that fit
+        // next to the cells - multiples of 8 keep the waves' shares of a window even
         const int nb = cu_count();
         int nblk8 = 0, nblk4 = 0;
         split_blocks((int)units8, (int)units4, nb, nblk8, nblk4);
-        int share = 1;
-        if (nblk8) share = std::max(share, ceil_div((int)units8, nblk8));
-        if (nblk4) share = std::max(share, ceil_div((int)units4, nblk4));
-        const int tcap = ceil_div(share, 4) + 1;
+        // virtual tiles of a block, exactly: the full rounds of whole tiles plus the one made of left-over
+        // quarter tiles (every byte of LDS counts here: it decides the width of the windows)
+        auto vtiles = [](int ntiles, int nblk) { return nblk ? ntiles / nblk + (ntiles % nblk ? 1 : 0) : 0; };
+        const int tcap = std::max(1, std::max(vtiles(p.ntiles8, nblk8), vtiles(p.ntiles4, nblk4)));
         if ((long long)tcap * nquads * nquads >= (1ll << 31)) return false;
-        for (int wq : {16, 12, 8, 4, 2, 1}) {
-            const size_t lds = scales + (size_t)p.M * (wq * 4 * G + A_PAD) + (size_t)tcap * NW * o.nr * 256;
+        for (int wq : {16, 12, 8, 4, 2}) {   // (even: a window's row is whole pieces of 1 KB, but for the end of K)
+            const size_t lds = scales + 2 * (size_t)p.M * (wq * 4 * G + A_PAD) + (size_t)tcap * NW * o.nr * 256;
             if (lds > LDS_LIMIT) continue;
             o.nblk8 = nblk8;
             o.nblk4 = nblk4;

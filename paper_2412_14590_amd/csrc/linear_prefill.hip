@@ -956,8 +956,11 @@ static int launch_shape(const LinearParams &p, hipStream_t st)
     return (int)hipErrorInvalidValue;
 }
 
-// token tiles (of 32) per wave: 4 = blocks of 128 x 128, 2 = 64 x 128, 1 = 32 x 128
-static int token_tiles_per_wave(const LinearParams &p)
+static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &qpp);
+
+// token tiles (of 32) per wave: 4 = blocks of 128 x 128, 2 = 64 x 128, 1 = 32 x 128.
+// `scratch_bytes` = the scratch the launch may split K with (0 = none).
+static int token_tiles_per_wave(const LinearParams &p, size_t scratch_bytes)
 {
     // variants only built for one and two token tiles per wave: group-wise activation scales; the debug
     // sums with group-wise 8-bit scales
@@ -965,7 +968,19 @@ static int token_tiles_per_wave(const LinearParams &p)
     if (p.prefill_tm) return (p.prefill_tm == 4 && group_scaled_acts) ? 0 : p.prefill_tm;   // the caller's choice (tests, benchmarks)
     const long nbn = (p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
     const long tiles128 = (long)((p.M + 127) / 128) * nbn, tiles64 = (long)((p.M + 63) / 64) * nbn;
-    if (3 * tiles64 <= 2 * cu_count() || p.M <= 32) return 1;          // (never a block taller than the batch)
+    if (3 * tiles64 <= 2 * cu_count() || p.M <= 32) {                  // (never a block taller than the batch)
+        // Where K is split over blocks the serial chain of groups in a block sets the time, and with
+        // 33..64 tokens a grid of 64-row blocks is half as many blocks, which may be cut into more
+        // K parts: the taller block when that leaves fewer groups per part (K = 28672, N = 8192:
+        // 49 against 61 us at 33 tokens, 55 against 66 at 64; K = 14336, N = 4096 gets eight parts
+        // either way and is 3 us faster with the 32-row blocks).
+        if (p.M > 32 && scratch_bytes) {
+            int q1, q2;
+            const int k1 = choose_kparts(p, 1, scratch_bytes, q1), k2 = choose_kparts(p, 2, scratch_bytes, q2);
+            if (k1 > 1 && k2 > 1 && q2 < q1) return 2;
+        }
+        return 1;
+    }
     if (3 * tiles128 <= 2 * cu_count() || group_scaled_acts || p.M <= 64) return 2;
     return 4;
 }
@@ -978,7 +993,7 @@ bool prefill_covers(const LinearParams &p)
     if ((size_t)p.M * (size_t)p.K >= lim || (size_t)p.ntiles4 * TILE_N * (size_t)p.K / 2 >= lim ||
         (size_t)p.ntiles8 * TILE_N * (size_t)p.K >= lim)
         return false;
-    return p.M >= 1 && p.N >= 1 && token_tiles_per_wave(p) != 0;
+    return p.M >= 1 && p.N >= 1 && token_tiles_per_wave(p, 0) != 0;
 }
 
 // K split.  A block walks its K range serially, and on layers with a long K (the down projections)
@@ -987,7 +1002,7 @@ bool prefill_covers(const LinearParams &p)
 // K range is cut into `kparts` parts for as many blocks (whole groups of 4 quantization groups, at
 // least two of them per part, at most about two blocks per CU in all); the parts' fp32 sums meet in
 // the caller's scratch (prefill_reduce_kernel), which costs a second launch and 8 bytes of traffic
-// per part and output, so it is kept under 12 MB of sums.  Measured (Llama-3-8B down projection,
+// per part and output, so it is kept under 16 MB of sums.  Measured (Llama-3-8B down projection,
 // K = 14336, N = 4096): 58 -> 22 us at 32 tokens, 56 -> 23 at 64, 56 -> 34 at 128, 55 -> 46 at
 // 256; Llama-3.1-70B (K = 28672, N = 8192): 124 -> 46 at 32, 119 -> 88 at 128.  With K <= 4096
 // there is nothing to gain: of the 14 us a 32 x 128 block of 32 groups lives, 4 us do not shrink with
@@ -1007,8 +1022,11 @@ static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &q
     const PrefillGrid g = grid_of(p, 32 * tm, tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128);
     const long blocks = (long)g.nbm4 * g.nb4 + (long)g.nbm8 * g.nb8, slots = 2L * cu_count();
     const size_t part_bytes = (size_t)p.M * p.np * sizeof(float);
-    long kp = std::min<long>(MAX_KPARTS, std::min<long>((slots + blocks / 2) / blocks, quads / 2));
-    kp = std::min<long>(kp, (long)(std::min<size_t>(cap_bytes, (size_t)12 << 20) / part_bytes));
+    // (blocks of 64 rows and more run two to a CU: one part too many and the launch takes a second
+    // round - K = 28672, N = 8192 at 33..64 tokens is 65 blocks, 43 us in 7 parts, 49 in 8; the
+    // 32-row blocks fit more to a CU and measured best with the count rounded to nearest)
+    long kp = std::min<long>(MAX_KPARTS, std::min<long>(tm >= 2 ? slots / blocks : (slots + blocks / 2) / blocks, quads / 2));
+    kp = std::min<long>(kp, (long)(std::min<size_t>(cap_bytes, (size_t)16 << 20) / part_bytes));
     if (forced) kp = std::min<long>(std::min<long>(atol(forced), MAX_KPARTS), std::min<long>(quads, (long)(cap_bytes / part_bytes)));
     if (kp <= 1) return 1;
     qpp = (int)((quads + kp - 1) / kp);
@@ -1019,14 +1037,14 @@ static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &q
 bool prefill_would_split(const LinearParams &p)
 {
     int qpp;
-    return prefill_covers(p) && p.partials && choose_kparts(p, token_tiles_per_wave(p), p.partials_cap, qpp) > 1;
+    return prefill_covers(p) && p.partials && choose_kparts(p, token_tiles_per_wave(p, p.partials_cap), p.partials_cap, qpp) > 1;
 }
 
 size_t prefill_scratch_bytes(const LinearParams &p)
 {
     if (!prefill_covers(p)) return 0;
     int qpp;
-    const int kp = choose_kparts(p, token_tiles_per_wave(p), ~(size_t)0, qpp);
+    const int kp = choose_kparts(p, token_tiles_per_wave(p, ~(size_t)0), ~(size_t)0, qpp);
     return kp > 1 ? (size_t)kp * p.M * p.np * sizeof(float) : 0;
 }
 
@@ -1037,7 +1055,8 @@ int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
     LinearParams p = p0;
     p.kparts = 1;
     p.quads_per_part = (p.ng + 3) / 4;
-    if (p.partials) p.kparts = choose_kparts(p, token_tiles_per_wave(p), p.partials_cap, p.quads_per_part);
+    const int tm = token_tiles_per_wave(p, p.partials ? p.partials_cap : 0);
+    if (p.partials) p.kparts = choose_kparts(p, tm, p.partials_cap, p.quads_per_part);
     // 128 x 128, 4 waves, wave tile 128 x 32 (a 128 x 256 block of 8 waves measured 5 % slower).
     // Where that grid has clearly less than one block per CU the chip is short of waves, not of rate:
     // blocks of 64 x 128 (wave tile 64 x 32) or 32 x 128 (wave tile 32 x 32) double the waves and
@@ -1047,7 +1066,7 @@ int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
     // chosen here: 25.6 -> 14.1 us at M = 128, 25.7 -> 15.7 at M = 256, 26.2 -> 20.9 at M = 512; K = 14336
     // (K not split): 76 -> 43, 76 -> 48, 76 -> 62.  With 192 blocks of 128 x 128 (N = 6144, M = 512) and
     // with 224 (N = 28672, M = 128) the shapes are within 2 % of each other.
-    switch (token_tiles_per_wave(p)) {
+    switch (tm) {
     case 1: return launch_shape<Shape<1, 4, 1, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
     case 2: return launch_shape<Shape<1, 4, 2, MIXLLM_PREFILL_WD_SMALL>, 2>(p, st);
     default: return launch_shape<Shape<1, MIXLLM_PREFILL_WN_LARGE, 4, MIXLLM_PREFILL_WD_LARGE>, 2>(p, st);
@@ -1061,7 +1080,7 @@ int launch_linear_prefill(const LinearParams &p0, hipStream_t st)
 bool prefill_plan(const LinearParams &p, int out[13])
 {
     if (!prefill_covers(p)) return false;
-    const int tm = token_tiles_per_wave(p);
+    const int tm = token_tiles_per_wave(p, ~(size_t)0);   // (the plan of a launch that has the scratch to split K)
     const int BM = 32 * tm, BN = tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128;
     const PrefillGrid g = grid_of(p, BM, BN);
     out[0] = BM;

@@ -133,9 +133,9 @@ def test_decode_split_plan_covers_every_channel_once(K, N, n8):
         nblk8, nblk4, tcap, lds, nwin, wq = p[:6]
         assert lds <= 160 * 1024
         nquads = (K // 128 + 3) // 4
-        if M * K > 131072:             # staged window by window: one block per CU, a window's row is at most 512 pieces
-            assert nblk8 + nblk4 <= 256 and wq in (16, 12, 8, 4, 2, 1) and nwin == -(-nquads // wq) >= 2
-            assert lds >= M * (wq * 512 + 16) + tcap * 8 * 4 * 256
+        if M * K > 131072:             # staged window by window in two buffers: one block per CU, whole pieces of 1 KB per row
+            assert nblk8 + nblk4 <= 256 and wq in (16, 12, 8, 4, 2) and nwin == -(-nquads // wq) >= 2
+            assert lds >= 2 * M * (wq * 512 + 16) + tcap * 8 * 4 * 256
             for nvt in range(1, tcap + 1):
                 check_windowed_chunk_lists(nvt, nquads, nwin, wq)
         else:
@@ -177,7 +177,7 @@ def check_prefill_grid(M, K, N, n8, act_group=None):
     if kparts > 1:
         ntile = nbm * nb4 + nbm8 * nb8
         assert ng >= 64 and groups_per_part >= 8 and ntile * kparts <= 2 * 256 + ntile // 2
-        assert kparts * M * (t8 + t4) * 16 * 4 <= 12 << 20
+        assert kparts * M * (t8 + t4) * 16 * 4 <= 16 << 20
     assert BM <= 32 or M > 32
     assert BM in (32, 64, 128) and BN == 128
     assert nbm == -(-M // BM) and nb8 == -(-t8 * 16 // BN) and nb4 == -(-t4 * 16 // BN)
