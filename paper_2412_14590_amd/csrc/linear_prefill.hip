@@ -969,19 +969,36 @@ static int token_tiles_per_wave(const LinearParams &p, size_t scratch_bytes)
     const long nbn = (p.ntiles8 * TILE_N + 127) / 128 + (p.ntiles4 * TILE_N + 127) / 128;
     const long tiles128 = (long)((p.M + 127) / 128) * nbn, tiles64 = (long)((p.M + 63) / 64) * nbn;
     if (3 * tiles64 <= 2 * cu_count() || p.M <= 32) {                  // (never a block taller than the batch)
-        // Where K is split over blocks the serial chain of groups in a block sets the time, and with
-        // 33..64 tokens a grid of 64-row blocks is half as many blocks, which may be cut into more
-        // K parts: the taller block when that leaves fewer groups per part (K = 28672, N = 8192:
-        // 49 against 61 us at 33 tokens, 55 against 66 at 64; K = 14336, N = 4096 gets eight parts
-        // either way and is 3 us faster with the 32-row blocks).
-        if (p.M > 32 && scratch_bytes) {
-            int q1, q2;
-            const int k1 = choose_kparts(p, 1, scratch_bytes, q1), k2 = choose_kparts(p, 2, scratch_bytes, q2);
-            if (k1 > 1 && k2 > 1 && q2 < q1) return 2;
+        // A grid this small is a race of serial chains: a block walks its quantization groups one
+        // after the other, and the launch takes as long as the busiest CU.  32-row or 64-row blocks,
+        // with the K split each would get, by
+        //   blocks on the busiest CU (a second one half hidden behind the first)
+        //     x groups of 4 per part x cost of a group of 4 in that block,
+        //   + 4 where a second kernel adds the parts up, + 1.5 for the heavier start of a 64-row block
+        // in units of a 32-row block's group of 4 (about 1.1 us; 1.25 for a 64-row block's).  Fitted
+        // to the Llama-shaped layers with the weights read from HBM: K = 28672, N = 8192 at 33 tokens
+        // 61 us in 32-row blocks of 4 parts, 41 in 64-row blocks of 7; K = 14336, N = 4096 at 256
+        // tokens 46 unsplit in 32-row blocks, 39 in 64-row blocks of 3 parts, but at 64 tokens 21
+        // against 25 (eight parts either way); K = N = 8192 at 96 tokens 26 unsplit in 32-row blocks,
+        // 28 in 64-row blocks of 3 parts; K = 8192, N = 10240 at 128 tokens without scratch 38 in
+        // 324 blocks of 32 rows, 32 in 162 of 64; K = N = 4096 at 256 tokens 15.8 in 264 blocks of 32
+        // rows, 17.4 in 132 of 64.
+        if (p.M > 32) {
+            const long cus = cu_count(), quads = (p.ng + 3) / 4;
+            auto cost = [&](int tm, long blocks) {
+                int qpp = (int)quads;
+                const int kp = scratch_bytes ? choose_kparts(p, tm, scratch_bytes, qpp) : 1;
+                const long on_a_cu = std::max(1L, (blocks * kp + cus - 1 - cus / 10) / cus);   // (a tenth of the CUs with one more block does not count)
+                return (1.0 + 0.5 * (double)(on_a_cu - 1)) * qpp * (tm == 2 ? 1.25 : 1.0) + (kp > 1 ? 4.0 : 0.0) + (tm == 2 ? 1.5 : 0.0);
+            };
+            if (cost(2, tiles64) < cost(1, (long)((p.M + 31) / 32) * nbn)) return 2;
         }
         return 1;
     }
     if (3 * tiles128 <= 2 * cu_count() || group_scaled_acts || p.M <= 64) return 2;
+    // (a last 128-row block that is at most half full is a quarter more work than 64-row blocks have:
+    // K = 4096, N = 28672 at 192 tokens 48 us in 128-row blocks, 44.5 in 64-row blocks)
+    if ((long)((p.M + 127) / 128) * 128 * 4 > (long)((p.M + 63) / 64) * 64 * 5) return 2;
     return 4;
 }
 
@@ -1020,11 +1037,14 @@ static int choose_kparts(const LinearParams &p, int tm, size_t cap_bytes, int &q
 #endif
     if (p.P || p.S || (p.ng < 64 && !forced)) return 1;
     const PrefillGrid g = grid_of(p, 32 * tm, tm == 4 ? 32 * MIXLLM_PREFILL_WN_LARGE : 128);
-    const long blocks = (long)g.nbm4 * g.nb4 + (long)g.nbm8 * g.nb8, slots = 2L * cu_count();
+    const long blocks = (long)g.nbm4 * g.nb4 + (long)g.nbm8 * g.nb8, slots = 2L * cu_count();   // (three 32-row blocks fit a CU, but counting on that split the wide K = 8192 layers in two and cost them 10 %)
     const size_t part_bytes = (size_t)p.M * p.np * sizeof(float);
     // (blocks of 64 rows and more run two to a CU: one part too many and the launch takes a second
     // round - K = 28672, N = 8192 at 33..64 tokens is 65 blocks, 43 us in 7 parts, 49 in 8; the
     // 32-row blocks fit more to a CU and measured best with the count rounded to nearest)
+    // A grid of more than 0.6 blocks per CU is not split: K = N = 8192 at 96 tokens (195 blocks) 28 us
+    // unsplit, 33 in three parts; at 192 tokens 33 against 39.
+    if (10 * blocks > 6L * cu_count() && !forced) return 1;
     long kp = std::min<long>(MAX_KPARTS, std::min<long>(tm >= 2 ? slots / blocks : (slots + blocks / 2) / blocks, quads / 2));
     kp = std::min<long>(kp, (long)(std::min<size_t>(cap_bytes, (size_t)16 << 20) / part_bytes));
     if (forced) kp = std::min<long>(std::min<long>(atol(forced), MAX_KPARTS), std::min<long>(quads, (long)(cap_bytes / part_bytes)));

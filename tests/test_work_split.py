@@ -170,7 +170,7 @@ def check_prefill_grid(M, K, N, n8, act_group=None):
     t8, t4 = tiles(N, n8)
     # K split over blocks (when the caller brings the scratch): whole groups of 4 quantization groups per
     # part, the parts cover K exactly, no part is empty; only layers with a long K are split, into at
-    # most about two blocks per CU in all, and the parts' sums stay under 12 MB
+    # most about two blocks per CU in all, and the parts' sums stay under 16 MB
     ng = K // 128
     assert 1 <= kparts <= 8 and groups_per_part % 4 == 0
     assert (kparts - 1) * groups_per_part < ng <= kparts * groups_per_part
