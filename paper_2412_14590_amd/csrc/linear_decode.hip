@@ -653,10 +653,9 @@ int launch_linear_decode(const LinearParams &p, hipStream_t st)
 {
     if (p.M == 0 || p.N == 0) return hipSuccess;
     if (decode_split_covers(p) && (prefer_split(p) || (p.x && !resident_can_fuse(p)))) return launch_linear_decode_split(p, st);
-    // Shapes the split variant cannot stage (M K > 64 Ki, e.g. 16 tokens with K >= 8192): the kernel for
-    // a few dozen tokens stages the activations per K step and measured 10-25 % faster than the streaming
-    // variant on layers of at least two tiles per CU (Llama-3.1-70B shapes, M = 16: 16.7 vs 20.7, 16.1 vs
-    // 19.0, 56.9 vs 63.7, 48.1 vs 58.9 us), slower on smaller ones (one tile per CU: 30 vs 20 us).
+    // Shapes the split variant does not take (one to four tokens of K > 32768): the kernel for a few
+    // dozen tokens stages the activations per K step and measured 10-25 % faster than the streaming
+    // variant on layers of at least two tiles per CU, slower on smaller ones (one tile per CU: 30 vs 20 us).
     if (p.variant == DECODE_ANY && !p.x && p.ntiles8 + p.ntiles4 >= 512 && mid_covers(p)) return launch_linear_mid(p, st);
     if (p.x) {   // fused quantizer
         if (!resident_can_fuse(p)) return (int)hipErrorInvalidValue;
