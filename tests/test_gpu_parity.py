@@ -195,7 +195,9 @@ def check_partials(M, K, N, n8, path, seed=24):
                                      (5, 384, 40, 40), (2, 2048, 2070, 207), (4, 14336, 100, 12), (4, 28672, 48, 5),
                                      # more than 128 Ki activation values: the split variant walks K in windows
                                      # (14336: 16 + 12 chunk columns; 9088: 16 + 2, the last group alone in its chunk)
-                                     (16, 14336, 100, 12), (9, 28672, 48, 5), (15, 9088, 70, 7)])
+                                     (16, 14336, 100, 12), (9, 28672, 48, 5), (15, 9088, 70, 7),
+                                     # the last window is one chunk column of which a quarter lies inside K
+                                     (16, 28800, 40, 4)])
 @pytest.mark.parametrize("path", ["generic", "decode"] + DECODE_VARIANTS)
 def test_group_partials_bit_exact_small_m(M, K, N, n8, path):
     say("partials", path, M, K, N, n8)
@@ -279,7 +281,8 @@ def check_linear(M, K, N, n8, path, variant="baseline", seed=25):
                                      (8, 14336, 272, 27), (3, 128, 33, 3), (2, 2048, 2070, 207), (1, 14336, 1000, 90),
                                      (4, 28672, 48, 5), (3, 32768, 40, 4),
                                      # the split variant with the activations staged window by window
-                                     (16, 14336, 272, 27), (10, 14336, 1000, 0), (16, 9088, 70, 70), (6, 28672, 48, 5)])
+                                     (16, 14336, 272, 27), (10, 14336, 1000, 0), (16, 9088, 70, 70), (6, 28672, 48, 5),
+                                     (16, 28800, 40, 4), (5, 28672, 8200, 820)])
 def test_linear_small_m(M, K, N, n8, path, variant):
     skip_unless_covered(path, M, K)
     check_linear(M, K, N, n8, path, variant)
