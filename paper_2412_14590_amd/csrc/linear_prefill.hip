@@ -56,11 +56,13 @@ constexpr int NSTAGE = 4;   // LDS stages of the activation tile (one group each
 #ifndef MIXLLM_PREFILL_L8
 #define MIXLLM_PREFILL_L8 3
 #endif
-// 1: in a launch of 128 x 128 blocks that is at most two rounds of blocks long, the 8-bit part runs in
-// blocks of 64 x 128 (0: never).  Measured at 2048 tokens, same machine, equal against half-height
-// 8-bit tiles: K = N = 4096 56.2 -> 51.5 us, K = 14336, N = 4096 164.5 -> 157.6, K = 4096, N = 6144
-// 75.4 -> 76.0; the layer of N = 28672 (seven rounds) 313 -> 324 us, which is why long launches keep
-// the full tiles; blocks of 32 x 128 for the 8-bit part of a 64 x 128 launch measured 4-7 % slower.
+// 1: in a launch of 128 x 128 blocks that is at most MIXLLM_PREFILL_HALF8_ROUNDS rounds of blocks long,
+// the 8-bit part runs in blocks of 64 x 128 (0: never).  Measured at 2048 tokens, same machine, equal
+// against half-height 8-bit tiles: K = N = 4096 56.2 -> 51.5 us, K = 14336, N = 4096 164.5 -> 157.6,
+// K = 4096, N = 6144 75.4 -> 76.0; at 4096 tokens (two to three rounds) 101.5 -> 98, 302 -> 297 and
+// 149 -> 143 us; the layer of N = 28672 gains 2 % at 1024 tokens (3.5 rounds), nothing at 2048 (seven:
+// 313 -> 324 us in one session, 330 -> 328 in another) and loses 1 % at 4096, which is why long launches
+// keep the full tiles; blocks of 32 x 128 for the 8-bit part of a 64 x 128 launch measured 4-7 % slower.
 #ifndef MIXLLM_PREFILL_HALF8
 #define MIXLLM_PREFILL_HALF8 1
 #endif
@@ -781,7 +783,7 @@ __global__ __launch_bounds__(C::THREADS, MINW) void linear_prefill_kernel(Linear
     // ids followed by a contiguous range of the 8-bit ids, so that every XCD ends on the cheap
     // tiles: 4-bit tiles take about twice as long as 8-bit ones (unpack, per-group rescale), and
     // the cheap ones fill the last, partly empty round of the grid.
-    // Where the host says so (half8: a launch of 128 x 128 blocks at most two rounds long) the 8-bit
+    // Where the host says so (half8: a launch of 128 x 128 blocks at most four rounds long) the 8-bit
     // tiles are half as tall as the 4-bit ones (C::Half).  Blocks are dispatched in the order of
     // their ids, so the 8-bit blocks - the last of every XCD - are what runs while the last 4-bit
     // blocks finish, and the finer they are the less of the chip idles then: with N = 4096 and 10 %
@@ -901,7 +903,7 @@ static int launch_variant(K kernel, bool with_sa, dim3 grid, dim3 block, hipStre
 }
 
 // the grid of a launch: token tiles of either part (BM rows for the 4-bit part; for the 8-bit part
-// half of that where a launch of 128 x 128 blocks is at most two rounds of blocks long), channel
+// half of that where a launch of 128 x 128 blocks is at most four rounds of blocks long), channel
 // tiles of either part, logical block ids per XCD of either part, token tiles per band of either part
 // (see linear_prefill_kernel)
 struct PrefillGrid {
@@ -913,7 +915,10 @@ static PrefillGrid grid_of(const LinearParams &p, int BM, int BN)
     g.nbm4 = (p.M + BM - 1) / BM;
     g.nb8 = (p.ntiles8 * TILE_N + BN - 1) / BN;
     g.nb4 = (p.ntiles4 * TILE_N + BN - 1) / BN;
-    const bool half8 = MIXLLM_PREFILL_HALF8 && BM == 128 && ((long)g.nbm4 * (g.nb4 + g.nb8) <= 4L * cu_count() || !p.w8_per_channel || p.P);
+#ifndef MIXLLM_PREFILL_HALF8_ROUNDS
+#define MIXLLM_PREFILL_HALF8_ROUNDS 4   // launches of up to this many rounds of 128 x 128 blocks (two per CU) run their 8-bit part in half-height blocks
+#endif
+    const bool half8 = MIXLLM_PREFILL_HALF8 && BM == 128 && ((long)g.nbm4 * (g.nb4 + g.nb8) <= 2L * MIXLLM_PREFILL_HALF8_ROUNDS * cu_count() || !p.w8_per_channel || p.P);
     g.bm8 = half8 ? BM / 2 : BM;
     g.nbm8 = (p.M + g.bm8 - 1) / g.bm8;
     g.per4 = (g.nbm4 * g.nb4 + 7) / 8;

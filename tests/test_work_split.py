@@ -181,9 +181,9 @@ def check_prefill_grid(M, K, N, n8, act_group=None):
     assert BM <= 32 or M > 32
     assert BM in (32, 64, 128) and BN == 128
     assert nbm == -(-M // BM) and nb8 == -(-t8 * 16 // BN) and nb4 == -(-t4 * 16 // BN)
-    # in a launch of 128 x 128 blocks at most two rounds of blocks long (two blocks per CU at a time) the
+    # in a launch of 128 x 128 blocks at most four rounds of blocks long (two blocks per CU at a time) the
     # 8-bit part runs in tiles half as tall, banded over the same token rows
-    assert BM8 == (64 if BM == 128 and nbm * (nb8 + nb4) <= 4 * 256 else BM)
+    assert BM8 == (64 if BM == 128 and nbm * (nb8 + nb4) <= 8 * 256 else BM)
     assert nbm8 == -(-M // BM8) and 1 <= band8 <= min(4 * BM // BM8, nbm8)
     assert 1 <= band <= min(4, nbm) and lds <= 80 * 1024 and blocks % 8 == 0
     # the shape rule: the largest block tile whose grid still has about one block per CU or more
