@@ -24,7 +24,9 @@
 //    are issued and awaited by hand (async_loads.h): left to the compiler they are moved next to
 //    their first use, and the ring collapses to one request at a time;
 //  * the int8 activations sit in LDS, staged once per block (with fp16 input of up to 16 Ki
-//    values the block runs the activation quantizer itself, same arithmetic, identical codes);
+//    values the block runs the activation quantizer itself, same arithmetic, identical codes;
+//    more than 128 Ki values - 5..16 tokens of a long K - pass through two LDS buffers in windows
+//    over K, see WIN below);
 //  * the zero point is hoisted out of the unpack, sum a (q - z) = sum a q - z sum a, with
 //    sum a from an MFMA against an all-ones operand (int32-exact);
 //  * a wave adds each chunk's contribution to its own LDS cell of the chunk's virtual tile;
